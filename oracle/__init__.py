@@ -1,0 +1,152 @@
+"""CheckFree recovery -- CPU oracle (numpy front end of oracle/cf_oracle.c).
+
+TEST INFRASTRUCTURE, NOT A PRODUCT PATH: imported only by tests/, by the smoke
+check and by the benchmark's CPU-baseline leg.  It imports nothing from the HIP
+package and the HIP package imports nothing from here.
+
+A *stage* is an ordered list of numpy arrays, one per weight (or gradient)
+tensor, exactly the paper's "combination of weights of the layers in that
+stage" (section "Problem Statement", paragraph "Distributed Training").
+dtype float32 is fp32; dtype uint16 holds bfloat16 bit patterns.
+
+Functions (paper: section "CheckFree: Memoryless Recovery", its display
+equation and Algorithm 1; section "CheckFree+: First and Last Stage Recovery"):
+
+  stage_grad_sqnorm(grads)                    omega_i = ||grad W^S_i||^2
+  effective_omega(w_prev, w_next)             weights used, incl. the degenerate rule
+  recover_stage_weighted_avg(prev, next, ..)  W^S_i = (w_{i-1} W_{i-1} + w_{i+1} W_{i+1}) / (w_{i-1} + w_{i+1})
+  blend_unrounded(prev, next, ..)             the same value in binary64, not narrowed
+  copy_stage(src)                             bytewise copy (CheckFree+)
+"""
+import ctypes
+import os
+
+import numpy as np
+
+from . import build_oracle
+
+_LIB = None
+
+
+def _lib():
+    global _LIB
+    if _LIB is None:
+        path = build_oracle.build(force=False)
+        lib = ctypes.CDLL(path)
+        c_dp = ctypes.POINTER(ctypes.c_double)
+        lib.cfo_sqnorm_f32.restype = ctypes.c_double
+        lib.cfo_sqnorm_f32.argtypes = [ctypes.c_void_p, ctypes.c_uint64]
+        lib.cfo_stage_sqnorm_f32.restype = ctypes.c_double
+        lib.cfo_stage_sqnorm_f32.argtypes = [ctypes.c_void_p, ctypes.c_void_p, ctypes.c_uint32]
+        lib.cfo_stage_sqnorm_f32_mt.restype = ctypes.c_double
+        lib.cfo_stage_sqnorm_f32_mt.argtypes = [ctypes.c_void_p, ctypes.c_void_p, ctypes.c_uint32,
+                                                ctypes.c_int]
+        lib.cfo_effective_omega.restype = ctypes.c_int
+        lib.cfo_effective_omega.argtypes = [ctypes.c_double, ctypes.c_double, c_dp, c_dp]
+        for name in ("cfo_blend_f32", "cfo_blend_bf16"):
+            fn = getattr(lib, name)
+            fn.restype = None
+            fn.argtypes = [ctypes.c_double, ctypes.c_double, ctypes.c_void_p, ctypes.c_void_p,
+                           ctypes.c_void_p, ctypes.c_uint64, ctypes.c_int]
+        lib.cfo_blend_f64.restype = None
+        lib.cfo_blend_f64.argtypes = [ctypes.c_double, ctypes.c_double, ctypes.c_void_p,
+                                      ctypes.c_void_p, ctypes.c_void_p, ctypes.c_uint64]
+        lib.cfo_copy_bytes.restype = None
+        lib.cfo_copy_bytes.argtypes = [ctypes.c_void_p, ctypes.c_void_p, ctypes.c_uint64,
+                                       ctypes.c_int]
+        lib.cfo_bf16_to_f64.restype = ctypes.c_double
+        lib.cfo_bf16_to_f64.argtypes = [ctypes.c_uint16]
+        lib.cfo_f64_to_bf16.restype = ctypes.c_uint16
+        lib.cfo_f64_to_bf16.argtypes = [ctypes.c_double]
+        lib.cfo_max_threads.restype = ctypes.c_int
+        lib.cfo_max_threads.argtypes = []
+        _LIB = lib
+    return _LIB
+
+
+def max_threads() -> int:
+    """Threads OpenMP would use by default on this host."""
+    return int(_lib().cfo_max_threads())
+
+
+def _flat(a, dtype):
+    a = np.ascontiguousarray(a)
+    if a.dtype != dtype:
+        raise TypeError(f"expected {np.dtype(dtype)}, got {a.dtype}")
+    return a.reshape(-1)
+
+
+def stage_grad_sqnorm(grads, threads: int = 1) -> float:
+    """omega of one stage: sum over its tensors (list order) of the sum of
+    squares of every fp32 gradient element, accumulated in binary64."""
+    arrs = [_flat(g, np.float32) for g in grads]
+    n = len(arrs)
+    ptrs = (ctypes.c_void_p * max(n, 1))(*[a.ctypes.data for a in arrs])
+    lens = (ctypes.c_uint64 * max(n, 1))(*[a.size for a in arrs])
+    if threads <= 1:
+        return float(_lib().cfo_stage_sqnorm_f32(ptrs, lens, n))
+    return float(_lib().cfo_stage_sqnorm_f32_mt(ptrs, lens, n, int(threads)))
+
+
+def effective_omega(omega_prev: float, omega_next: float):
+    """(w_prev, w_next, degenerate): the weights the blend really uses."""
+    ep, en = ctypes.c_double(), ctypes.c_double()
+    flag = _lib().cfo_effective_omega(float(omega_prev), float(omega_next),
+                                      ctypes.byref(ep), ctypes.byref(en))
+    return ep.value, en.value, bool(flag)
+
+
+def recover_stage_weighted_avg(prev, next, omega_prev: float, omega_next: float,
+                               threads: int = 1):
+    """The lost stage: for every tensor pair of the two neighbouring stages the
+    elementwise weighted average with weights omega_prev, omega_next, computed
+    in binary64 and rounded once to the tensors' own type."""
+    if len(prev) != len(next):
+        raise ValueError("neighbouring stages differ in tensor count")
+    out = []
+    for a, b in zip(prev, next):
+        a = np.ascontiguousarray(a)
+        b = np.ascontiguousarray(b)
+        if a.shape != b.shape or a.dtype != b.dtype:
+            raise ValueError("neighbouring stages are not congruent")
+        o = np.empty_like(a)
+        if a.dtype == np.float32:
+            fn = _lib().cfo_blend_f32
+        elif a.dtype == np.uint16:
+            fn = _lib().cfo_blend_bf16
+        else:
+            raise TypeError(f"unsupported weight dtype {a.dtype}")
+        fn(float(omega_prev), float(omega_next), a.ctypes.data, b.ctypes.data, o.ctypes.data,
+           a.size, int(threads))
+        out.append(o)
+    return out
+
+
+def blend_unrounded(prev, next, omega_prev: float, omega_next: float):
+    """Binary64 value of the display equation for binary64 inputs, one array."""
+    a = _flat(prev, np.float64)
+    b = _flat(next, np.float64)
+    o = np.empty_like(a)
+    _lib().cfo_blend_f64(float(omega_prev), float(omega_next), a.ctypes.data, b.ctypes.data,
+                         o.ctypes.data, a.size)
+    return o.reshape(np.shape(prev))
+
+
+def copy_stage(src, threads: int = 1):
+    """CheckFree+ recovery of an end stage or of the (de)embedding: every tensor
+    reproduced bit for bit."""
+    out = []
+    for s in src:
+        s = np.ascontiguousarray(s)
+        d = np.empty_like(s)
+        _lib().cfo_copy_bytes(d.ctypes.data, s.ctypes.data, s.nbytes, int(threads))
+        out.append(d)
+    return out
+
+
+def bf16_to_f64(bits: int) -> float:
+    return float(_lib().cfo_bf16_to_f64(int(bits)))
+
+
+def f64_to_bf16(x: float) -> int:
+    return int(_lib().cfo_f64_to_bf16(float(x)))
