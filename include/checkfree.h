@@ -1,0 +1,221 @@
+/*
+ * checkfree.h -- C ABI of the CheckFree stage-recovery hot path on AMD CDNA4
+ * (gfx950), hand-written HIP behind plain C entry points.
+ *
+ * Paper: "All is Not Lost: LLM Recovery without Checkpoints" (CheckFree /
+ * CheckFree+).  A pipeline *stage* S_i holds a consecutive block of layers; its
+ * weights W^S_i are "the combination of weights of the layers in that stage"
+ * (section "Problem Statement", paragraph "Distributed Training").  Here a stage
+ * is an ordered list of contiguous device tensors.
+ *
+ * The three operations:
+ *
+ *   cf_stage_grad_sqnorm           omega_i = || grad W^S_i ||^2
+ *       (section "CheckFree: Memoryless Recovery": every stage keeps the squared
+ *       norm of its last gradient, one scalar, ready for a newcomer)
+ *
+ *   cf_recover_stage_weighted_avg  W^S_i = (omega_{i-1} W^S_{i-1} + omega_{i+1} W^S_{i+1})
+ *                                          / (omega_{i-1} + omega_{i+1})
+ *       (display equation of that section; Algorithm 1, third step)
+ *
+ *   cf_copy_stage                  W^S_dst = W^S_src, bit for bit
+ *       (section "CheckFree+: First and Last Stage Recovery": a first/last stage
+ *       is restored from its neighbour, embedding and de-embedding from the
+ *       replicas kept on the neighbouring stages, "exactly")
+ *
+ * General rules
+ *   - Every function returns a cf_status (0 = CF_OK, negative = error) and never
+ *     throws, aborts or exits.  Nothing is launched when an error is returned.
+ *   - Pointers named d_* and every cf_tensor.data are DEVICE pointers; everything
+ *     else is a HOST pointer.
+ *   - The library never allocates, frees or keeps alive tensor memory.  Handles
+ *     own only small tables (a few KB to a few hundred KB of device memory,
+ *     allocated when the handle is created).  The three hot calls allocate
+ *     nothing, copy nothing between host and device, and do not synchronise:
+ *     they enqueue work on the caller's stream and return.
+ *   - `stream` is a hipStream_t passed as void* (NULL = the default stream).
+ *   - A context serialises its calls through device-side bookkeeping: calls that
+ *     use the same cf_ctx must be ordered on one stream (or otherwise
+ *     serialised by the caller).  Use one context per concurrent stream.
+ *   - Data-dependent conditions cannot be returned synchronously; they raise
+ *     sticky bits in a device flag word read by cf_read_flags.
+ */
+#ifndef CHECKFREE_H
+#define CHECKFREE_H
+
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+#if defined(__GNUC__) || defined(__clang__)
+#define CF_API __attribute__((visibility("default")))
+#else
+#define CF_API
+#endif
+
+typedef int32_t cf_status;
+
+enum {
+    CF_OK = 0,
+    CF_ERR_NULL = -1,            /* a required pointer argument is NULL */
+    CF_ERR_SHAPE_MISMATCH = -2,  /* stages differ in tensor count, numel or dtype */
+    CF_ERR_DTYPE = -3,           /* unknown dtype, or a dtype the operation does not take */
+    CF_ERR_ALIGN = -4,           /* tensor data not aligned to its element size */
+    CF_ERR_LIMIT = -5,           /* a size exceeds what the library supports */
+    CF_ERR_HIP = -6,             /* a HIP runtime call failed (no device, bad stream, ...) */
+    CF_ERR_ALIAS = -7,           /* output tensors overlap inputs other than element for element */
+    CF_ERR_CONTEXT = -8          /* handles belong to different contexts */
+};
+
+/* Element types of stage tensors. */
+enum {
+    CF_F32 = 0,   /* IEEE binary32 */
+    CF_BF16 = 1   /* bfloat16 (upper half of a binary32) */
+};
+
+/* Sticky device flags (cf_read_flags). */
+enum {
+    CF_FLAG_DEGENERATE_OMEGA = 1u,  /* a recovery saw an unusable omega pair and used the uniform average */
+    CF_FLAG_NONFINITE_OMEGA = 2u    /* a squared norm came out Inf or NaN */
+};
+
+/* One contiguous tensor in device memory.  `data` must be aligned to the element
+ * size (16-byte alignment is not required; 16-byte aligned tensors take the fast
+ * path).  numel may be 0 (then data may be NULL). */
+typedef struct cf_tensor {
+    void *data;      /* device pointer */
+    uint64_t numel;  /* number of elements */
+    int32_t dtype;   /* CF_F32 or CF_BF16 */
+    int32_t reserved;
+} cf_tensor;
+
+/* Launch shape knobs.  Zero in any field keeps the default. */
+typedef struct cf_tuning {
+    uint32_t chunk_elems;          /* elements per work chunk; multiple of 2048, at most 2^20 */
+    uint32_t sqnorm_blocks_per_cu; /* resident 256-thread workgroups per compute unit */
+    uint32_t blend_blocks_per_cu;
+    uint32_t copy_blocks_per_cu;
+} cf_tuning;
+
+typedef struct cf_ctx cf_ctx;      /* opaque: per-device bookkeeping */
+typedef struct cf_stage cf_stage;  /* opaque: a stage's tensor list, uploaded once */
+
+/* ---- set-up (not on the hot path; may allocate small device tables and
+ *      synchronise) ---- */
+
+/* Creates a context on HIP device `device`.  `tuning` may be NULL.  Allocates a
+ * 256-byte device word block (ticket, flags).  Errors: CF_ERR_NULL, CF_ERR_HIP,
+ * CF_ERR_LIMIT (bad tuning value). */
+CF_API cf_status cf_ctx_create(int device, const cf_tuning *tuning, cf_ctx **out);
+
+/* Frees the context's device words.  Stages created from it must be destroyed
+ * first.  NULL is accepted. */
+CF_API cf_status cf_ctx_destroy(cf_ctx *ctx);
+
+/* Describes a stage: `tensors` is a HOST array of `num_tensors` descriptors,
+ * borrowed only for the duration of this call (its contents are copied).  The
+ * tensors' memory is borrowed for as long as the stage handle is used; the
+ * caller keeps it alive and at the same addresses.  num_tensors may be 0.
+ * Uploads the stage's chunk table with one blocking host-to-device copy.
+ * Errors: CF_ERR_NULL, CF_ERR_DTYPE, CF_ERR_ALIGN, CF_ERR_LIMIT (more than 2^31
+ * chunks), CF_ERR_HIP. */
+CF_API cf_status cf_stage_create(cf_ctx *ctx, const cf_tensor *tensors, uint32_t num_tensors, cf_stage **out);
+
+/* Frees the stage's tables (never the tensors).  NULL is accepted. */
+CF_API cf_status cf_stage_destroy(cf_stage *stage);
+
+/* Introspection; 0 for a NULL handle. */
+CF_API uint32_t cf_stage_num_tensors(const cf_stage *stage);
+CF_API uint64_t cf_stage_numel(const cf_stage *stage);   /* elements over all tensors */
+CF_API uint64_t cf_stage_nbytes(const cf_stage *stage);  /* bytes over all tensors */
+CF_API uint32_t cf_stage_num_chunks(const cf_stage *stage);
+
+/* ---- the hot path ---- */
+
+/* omega_s = sum over every tensor of grad_stages[s] of the sum of squares of its
+ * elements, for s = 0 .. n_stages-1, in ONE kernel launch (groups of at most 64
+ * stages per launch).  Paper: section "CheckFree: Memoryless Recovery",
+ * omega_i = ||grad W^S_i||^2; Algorithm 1, the two "Receive" steps.
+ *
+ *   grad_stages  HOST array of n_stages stage handles (all tensors CF_F32)
+ *   d_omega_out  DEVICE array of n_stages doubles, written by the kernel
+ *
+ * Elements are squared and accumulated in binary32 per lane, reduced per
+ * wavefront to one binary32 partial per (chunk, wavefront) at a fixed slot, and
+ * the partials of a stage are summed in binary64 in a fixed order by the last
+ * workgroup to finish: the result is bit-identical from run to run and does not
+ * depend on the launch shape.  An empty stage gives 0.  A non-finite result
+ * raises CF_FLAG_NONFINITE_OMEGA.  The same stage handle must not appear in two
+ * sqnorm calls that run concurrently.
+ * Errors: CF_ERR_NULL, CF_ERR_DTYPE, CF_ERR_CONTEXT, CF_ERR_LIMIT, CF_ERR_HIP. */
+CF_API cf_status cf_stage_grad_sqnorm(cf_ctx *ctx, const cf_stage *const *grad_stages, uint32_t n_stages,
+                               double *d_omega_out, void *stream);
+
+/* Rebuilds a lost intermediate stage from its two neighbours:
+ *   lost[t][k] = (w_p * prev[t][k] + w_n * next[t][k]) / (w_p + w_n)
+ * for every tensor t and element k, with w_p = *d_omega_prev, w_n = *d_omega_next
+ * read from DEVICE memory by the kernel (so the norms never visit the host).
+ * Paper: display equation of section "CheckFree: Memoryless Recovery"; Algorithm
+ * 1's third step prints omega_{i-1} on both terms, which contradicts the
+ * section's own special cases; the display equation is followed.
+ *
+ * Arithmetic per element: both products and their sum in binary64, each rounded
+ * separately (no fused multiply-add), times the binary64 reciprocal of
+ * (w_p + w_n), one rounding (nearest even) to the tensor's dtype.  Subnormals are
+ * kept.
+ *
+ * If the pair is unusable -- either omega negative, NaN or Inf, or their sum not
+ * a positive normal binary64 number -- both weights are replaced by 1 (the
+ * uniform average) and CF_FLAG_DEGENERATE_OMEGA is raised.
+ *
+ * prev, next and lost must agree tensor by tensor in numel and dtype
+ * (CF_ERR_SHAPE_MISMATCH).  A tensor of `lost` may be the very same memory as the
+ * corresponding tensor of prev or next; any other overlap is CF_ERR_ALIAS.
+ * Errors: CF_ERR_NULL, CF_ERR_SHAPE_MISMATCH, CF_ERR_ALIAS, CF_ERR_CONTEXT,
+ * CF_ERR_HIP. */
+CF_API cf_status cf_recover_stage_weighted_avg(cf_ctx *ctx, const cf_stage *prev, const cf_stage *next,
+                                        const double *d_omega_prev, const double *d_omega_next,
+                                        cf_stage *lost, void *stream);
+
+/* Copies every tensor of src into the corresponding tensor of dst, bit for bit
+ * (NaN payloads, signed zeros and subnormals included); bytes outside dst's
+ * tensors are not touched.  Paper: section "CheckFree+: First and Last Stage
+ * Recovery" (first/last stage from its neighbour; embedding, de-embedding from
+ * their replicas).  src and dst must agree in numel and dtype per tensor
+ * (CF_ERR_SHAPE_MISMATCH) and must not overlap unless identical (CF_ERR_ALIAS).
+ * Errors: CF_ERR_NULL, CF_ERR_SHAPE_MISMATCH, CF_ERR_ALIAS, CF_ERR_CONTEXT,
+ * CF_ERR_HIP. */
+CF_API cf_status cf_copy_stage(cf_ctx *ctx, const cf_stage *src, cf_stage *dst, void *stream);
+
+/* ---- after the fact ---- */
+
+/* Waits for `stream`, then copies the context's sticky flag word to *flags
+ * (HOST).  If `clear` is non-zero the device word is reset to 0 afterwards.
+ * Errors: CF_ERR_NULL, CF_ERR_HIP. */
+CF_API cf_status cf_read_flags(cf_ctx *ctx, void *stream, uint32_t *flags, int clear);
+
+/* ---- host-only helpers (no device needed) ---- */
+
+/* Number of work chunks a tensor list is cut into with `chunk_elems` elements per
+ * chunk (every tensor starts a new chunk; an empty tensor has none).  Returns
+ * UINT64_MAX on a NULL list with num_tensors > 0 or chunk_elems == 0. */
+CF_API uint64_t cf_plan_num_chunks(const cf_tensor *tensors, uint32_t num_tensors, uint32_t chunk_elems);
+
+/* Writes the chunk plan into HOST arrays of capacity `cap` chunks: the tensor
+ * each chunk belongs to, its first element and its length in elements.  Returns
+ * CF_ERR_LIMIT if cap is too small. */
+CF_API cf_status cf_plan_chunks(const cf_tensor *tensors, uint32_t num_tensors, uint32_t chunk_elems,
+                         uint32_t *chunk_tensor, uint64_t *chunk_first, uint32_t *chunk_len, uint64_t cap);
+
+/* The tuning values in effect when `tuning` is NULL or holds zeros. */
+CF_API void cf_default_tuning(cf_tuning *out);
+
+/* A static, human-readable name for a status code. */
+CF_API const char *cf_status_string(cf_status status);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* CHECKFREE_H */

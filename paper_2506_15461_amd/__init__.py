@@ -1,0 +1,287 @@
+"""CheckFree stage recovery on MI355X: thin Python binding of libcheckfree.so.
+
+Argument marshalling only -- every step of the path (squared gradient norms,
+norm-to-weight scaling, weighted-average blend, copy) runs in the HIP kernels
+behind the C ABI of include/checkfree.h.  PyTorch supplies device memory and
+streams.  There is no CPU fallback: without the built library every call here
+raises.
+
+Paper: "All is Not Lost: LLM Recovery without Checkpoints", sections "CheckFree:
+Memoryless Recovery" (omega_i = ||grad W^S_i||^2, the weighted-average display
+equation, Algorithm 1) and "CheckFree+: First and Last Stage Recovery".
+
+    ctx   = Context(0)
+    prev  = Stage(ctx, prev_weights);  nxt = Stage(ctx, next_weights);  lost = Stage(ctx, lost_weights)
+    gp    = Stage(ctx, prev_grads);    gn  = Stage(ctx, next_grads)
+    omega = cf_stage_grad_sqnorm(ctx, [gp, gn])            # float64[2], stays on the device
+    cf_recover_stage_weighted_avg(ctx, prev, nxt, omega[0:1], omega[1:2], lost)
+    cf_copy_stage(ctx, src, dst)                           # CheckFree+
+"""
+import ctypes
+import os
+
+_PKG = os.path.dirname(os.path.abspath(__file__))
+LIB_PATH = os.path.join(_PKG, "libcheckfree.so")
+
+CF_OK = 0
+CF_ERR_NULL, CF_ERR_SHAPE_MISMATCH, CF_ERR_DTYPE, CF_ERR_ALIGN = -1, -2, -3, -4
+CF_ERR_LIMIT, CF_ERR_HIP, CF_ERR_ALIAS, CF_ERR_CONTEXT = -5, -6, -7, -8
+CF_F32, CF_BF16 = 0, 1
+CF_FLAG_DEGENERATE_OMEGA, CF_FLAG_NONFINITE_OMEGA = 1, 2
+
+# Every symbol include/checkfree.h declares.
+EXPORTS = (
+    "cf_ctx_create", "cf_ctx_destroy", "cf_stage_create", "cf_stage_destroy",
+    "cf_stage_num_tensors", "cf_stage_numel", "cf_stage_nbytes", "cf_stage_num_chunks",
+    "cf_stage_grad_sqnorm", "cf_recover_stage_weighted_avg", "cf_copy_stage", "cf_read_flags",
+    "cf_plan_num_chunks", "cf_plan_chunks", "cf_default_tuning", "cf_status_string",
+)
+
+
+class CfTensor(ctypes.Structure):
+    _fields_ = [("data", ctypes.c_void_p), ("numel", ctypes.c_uint64),
+                ("dtype", ctypes.c_int32), ("reserved", ctypes.c_int32)]
+
+
+class CfTuning(ctypes.Structure):
+    _fields_ = [("chunk_elems", ctypes.c_uint32), ("sqnorm_blocks_per_cu", ctypes.c_uint32),
+                ("blend_blocks_per_cu", ctypes.c_uint32), ("copy_blocks_per_cu", ctypes.c_uint32)]
+
+
+class CheckFreeError(RuntimeError):
+    def __init__(self, status, what):
+        self.status = status
+        super().__init__(f"{what}: {status_string(status)} ({status})")
+
+
+_lib = None
+
+
+def load_library():
+    """Loads libcheckfree.so (once).  PyTorch is imported first so that the
+    library binds to the HIP runtime PyTorch already carries."""
+    global _lib
+    if _lib is not None:
+        return _lib
+    if not os.path.exists(LIB_PATH):
+        raise RuntimeError(
+            f"{LIB_PATH} is not built; run `python -c 'import __graft_entry__ as g; g.build()'` "
+            "(or `python paper_2506_15461_amd/build.py`).  There is no fallback path.")
+    try:
+        import torch  # noqa: F401  (brings in libamdhip64)
+    except Exception:
+        pass
+    lib = ctypes.CDLL(LIB_PATH)
+    vp, u32, u64, i32 = ctypes.c_void_p, ctypes.c_uint32, ctypes.c_uint64, ctypes.c_int32
+    lib.cf_ctx_create.restype = i32
+    lib.cf_ctx_create.argtypes = [ctypes.c_int, ctypes.POINTER(CfTuning), ctypes.POINTER(vp)]
+    lib.cf_ctx_destroy.restype = i32
+    lib.cf_ctx_destroy.argtypes = [vp]
+    lib.cf_stage_create.restype = i32
+    lib.cf_stage_create.argtypes = [vp, ctypes.POINTER(CfTensor), u32, ctypes.POINTER(vp)]
+    lib.cf_stage_destroy.restype = i32
+    lib.cf_stage_destroy.argtypes = [vp]
+    lib.cf_stage_num_tensors.restype = u32
+    lib.cf_stage_num_tensors.argtypes = [vp]
+    lib.cf_stage_numel.restype = u64
+    lib.cf_stage_numel.argtypes = [vp]
+    lib.cf_stage_nbytes.restype = u64
+    lib.cf_stage_nbytes.argtypes = [vp]
+    lib.cf_stage_num_chunks.restype = u32
+    lib.cf_stage_num_chunks.argtypes = [vp]
+    lib.cf_stage_grad_sqnorm.restype = i32
+    lib.cf_stage_grad_sqnorm.argtypes = [vp, ctypes.POINTER(vp), u32, vp, vp]
+    lib.cf_recover_stage_weighted_avg.restype = i32
+    lib.cf_recover_stage_weighted_avg.argtypes = [vp, vp, vp, vp, vp, vp, vp]
+    lib.cf_copy_stage.restype = i32
+    lib.cf_copy_stage.argtypes = [vp, vp, vp, vp]
+    lib.cf_read_flags.restype = i32
+    lib.cf_read_flags.argtypes = [vp, vp, ctypes.POINTER(u32), ctypes.c_int]
+    lib.cf_plan_num_chunks.restype = u64
+    lib.cf_plan_num_chunks.argtypes = [ctypes.POINTER(CfTensor), u32, u32]
+    lib.cf_plan_chunks.restype = i32
+    lib.cf_plan_chunks.argtypes = [ctypes.POINTER(CfTensor), u32, u32, ctypes.POINTER(u32),
+                                   ctypes.POINTER(u64), ctypes.POINTER(u32), u64]
+    lib.cf_default_tuning.restype = None
+    lib.cf_default_tuning.argtypes = [ctypes.POINTER(CfTuning)]
+    lib.cf_status_string.restype = ctypes.c_char_p
+    lib.cf_status_string.argtypes = [i32]
+    _lib = lib
+    return lib
+
+
+def status_string(status: int) -> str:
+    return load_library().cf_status_string(int(status)).decode()
+
+
+def _check(status, what):
+    if status != CF_OK:
+        raise CheckFreeError(status, what)
+
+
+def default_tuning() -> dict:
+    t = CfTuning()
+    load_library().cf_default_tuning(ctypes.byref(t))
+    return {name: getattr(t, name) for name, _ in CfTuning._fields_}
+
+
+def _stream_ptr(stream):
+    import torch
+    if stream is None:
+        stream = torch.cuda.current_stream()
+    if isinstance(stream, int):
+        return ctypes.c_void_p(stream)
+    return ctypes.c_void_p(stream.cuda_stream)
+
+
+def _dtype_code(t):
+    import torch
+    if t.dtype == torch.float32:
+        return CF_F32
+    if t.dtype == torch.bfloat16:
+        return CF_BF16
+    raise CheckFreeError(CF_ERR_DTYPE, f"tensor dtype {t.dtype}")
+
+
+def tensor_descriptors(tensors):
+    """ctypes array of cf_tensor for a list of contiguous torch tensors."""
+    arr = (CfTensor * max(len(tensors), 1))()
+    for i, t in enumerate(tensors):
+        if not t.is_contiguous():
+            raise ValueError("stage tensors must be contiguous")
+        arr[i].data = t.data_ptr() if t.numel() else None
+        arr[i].numel = t.numel()
+        arr[i].dtype = _dtype_code(t)
+        arr[i].reserved = 0
+    return arr
+
+
+class Context:
+    """cf_ctx: per-device bookkeeping (ticket and flag words).  One per stream."""
+
+    def __init__(self, device=0, **tuning):
+        import torch
+        self._h = ctypes.c_void_p()
+        self.device = torch.device("cuda", device) if isinstance(device, int) else torch.device(device)
+        index = self.device.index if self.device.index is not None else torch.cuda.current_device()
+        self.device = torch.device("cuda", index)
+        t = CfTuning(**{k: int(v) for k, v in tuning.items()}) if tuning else None
+        lib = load_library()
+        _check(lib.cf_ctx_create(index, ctypes.byref(t) if t is not None else None, ctypes.byref(self._h)),
+               "cf_ctx_create")
+
+    def read_flags(self, clear=False, stream=None) -> int:
+        out = ctypes.c_uint32(0)
+        _check(load_library().cf_read_flags(self._h, _stream_ptr(stream), ctypes.byref(out), int(bool(clear))),
+               "cf_read_flags")
+        return int(out.value)
+
+    def close(self):
+        if self._h:
+            load_library().cf_ctx_destroy(self._h)
+            self._h = ctypes.c_void_p()
+
+    def __del__(self):
+        try:
+            self.close()
+        except Exception:
+            pass
+
+
+class Stage:
+    """cf_stage: the tensor list of one pipeline stage (weights or gradients).
+    Keeps the tensors alive; the library only borrows their memory."""
+
+    def __init__(self, ctx: Context, tensors):
+        self.ctx = ctx
+        self.tensors = list(tensors)
+        for t in self.tensors:
+            if t.device != ctx.device:
+                raise ValueError(f"tensor on {t.device}, context on {ctx.device}")
+        self._h = ctypes.c_void_p()
+        desc = tensor_descriptors(self.tensors)
+        _check(load_library().cf_stage_create(ctx._h, desc, len(self.tensors), ctypes.byref(self._h)),
+               "cf_stage_create")
+
+    @property
+    def numel(self):
+        return int(load_library().cf_stage_numel(self._h))
+
+    @property
+    def nbytes(self):
+        return int(load_library().cf_stage_nbytes(self._h))
+
+    @property
+    def num_chunks(self):
+        return int(load_library().cf_stage_num_chunks(self._h))
+
+    def close(self):
+        if self._h:
+            load_library().cf_stage_destroy(self._h)
+            self._h = ctypes.c_void_p()
+
+    def __del__(self):
+        try:
+            self.close()
+        except Exception:
+            pass
+
+
+def cf_stage_grad_sqnorm(ctx: Context, grad_stages, out=None, stream=None):
+    """omega_s = ||grad W^S_s||^2 for every stage of `grad_stages`, one launch.
+    Returns a float64 device tensor of len(grad_stages) (written into `out` if
+    given).  Asynchronous on the stream."""
+    import torch
+    n = len(grad_stages)
+    if out is None:
+        out = torch.empty(n, dtype=torch.float64, device=ctx.device)
+    if out.dtype != torch.float64 or out.numel() < n or not out.is_contiguous() or out.device != ctx.device:
+        raise ValueError("out must be a contiguous float64 device tensor with one element per stage")
+    handles = (ctypes.c_void_p * max(n, 1))(*[s._h for s in grad_stages])
+    _check(load_library().cf_stage_grad_sqnorm(ctx._h, handles, n, ctypes.c_void_p(out.data_ptr()),
+                                               _stream_ptr(stream)), "cf_stage_grad_sqnorm")
+    return out
+
+
+def _omega_ptr(ctx, w):
+    import torch
+    if w.dtype != torch.float64 or w.numel() != 1 or w.device != ctx.device:
+        raise ValueError("omega must be a one-element float64 device tensor (e.g. omega[i:i+1])")
+    return ctypes.c_void_p(w.data_ptr())
+
+
+def cf_recover_stage_weighted_avg(ctx: Context, prev: Stage, next: Stage, omega_prev, omega_next,
+                                  lost: Stage, stream=None):
+    """lost <- (omega_prev * prev + omega_next * next) / (omega_prev + omega_next),
+    the omegas read from device memory by the kernel.  Asynchronous."""
+    _check(load_library().cf_recover_stage_weighted_avg(
+        ctx._h, prev._h, next._h, _omega_ptr(ctx, omega_prev), _omega_ptr(ctx, omega_next), lost._h,
+        _stream_ptr(stream)), "cf_recover_stage_weighted_avg")
+    return lost
+
+
+def cf_copy_stage(ctx: Context, src: Stage, dst: Stage, stream=None):
+    """dst <- src bit for bit (CheckFree+ end-stage / (de)embedding recovery)."""
+    _check(load_library().cf_copy_stage(ctx._h, src._h, dst._h, _stream_ptr(stream)), "cf_copy_stage")
+    return dst
+
+
+def plan_chunks(numels, chunk_elems, dtype=CF_F32):
+    """Host-only: the chunk plan (tensor index, first element, length) the
+    library would use for tensors of the given element counts."""
+    n = len(numels)
+    arr = (CfTensor * max(n, 1))()
+    for i, m in enumerate(numels):
+        arr[i].data = None
+        arr[i].numel = int(m)
+        arr[i].dtype = dtype
+    lib = load_library()
+    total = lib.cf_plan_num_chunks(arr, n, int(chunk_elems))
+    if total == 2 ** 64 - 1:
+        raise CheckFreeError(CF_ERR_LIMIT, "cf_plan_num_chunks")
+    cap = max(int(total), 1)
+    ct = (ctypes.c_uint32 * cap)()
+    cf = (ctypes.c_uint64 * cap)()
+    cl = (ctypes.c_uint32 * cap)()
+    _check(lib.cf_plan_chunks(arr, n, int(chunk_elems), ct, cf, cl, int(total)), "cf_plan_chunks")
+    return [(ct[i], cf[i], cl[i]) for i in range(int(total))]

@@ -1,0 +1,464 @@
+// Host side of the C ABI declared in include/checkfree.h: handles, validation,
+// chunk planning, launch-shape selection.  No arithmetic of the method lives
+// here; every step of the path runs in the kernels of cf_kernels.hip.
+#include <hip/hip_runtime_api.h>
+
+#include <algorithm>
+#include <atomic>
+#include <cstring>
+#include <new>
+#include <vector>
+
+#include "checkfree.h"
+#include "cf_kernels.h"
+
+namespace {
+
+constexpr uint32_t kDefaultChunkElems = 32768;   // 128 KiB of fp32 per chunk
+constexpr uint32_t kDefaultSqnormBlocksPerCu = 8;
+constexpr uint32_t kDefaultBlendBlocksPerCu = 8;
+constexpr uint32_t kDefaultCopyBlocksPerCu = 8;
+constexpr uint32_t kMaxChunkElems = 1u << 20;
+constexpr uint32_t kChunkElemsGranule = 2048;    // keeps chunk boundaries 16-byte aligned relative to the tensor start
+constexpr uint64_t kMaxChunksPerStage = 1ull << 31;
+constexpr size_t kCtxWordBytes = 256;
+
+std::atomic<uint64_t> g_next_stage_id{1};
+
+uint32_t elem_size(int32_t dtype) { return dtype == CF_F32 ? 4u : 2u; }
+
+struct HostTensor {
+    uint64_t addr;
+    uint64_t numel;
+    int32_t dtype;
+};
+
+}  // namespace
+
+struct cf_ctx {
+    int device = 0;
+    int num_cu = 0;
+    cf_tuning tuning{};
+    uint32_t *d_words = nullptr;
+    // Pairs (input stage id, output stage id) whose congruence and aliasing have been checked.
+    std::vector<std::pair<uint64_t, uint64_t>> checked;
+};
+
+struct cf_stage {
+    cf_ctx *ctx = nullptr;
+    uint64_t id = 0;
+    std::vector<HostTensor> tensors;
+    uint64_t numel = 0;
+    uint64_t nbytes = 0;
+    uint32_t n_chunks = 0;
+    bool all_f32 = true;
+    CfChunk *d_chunks = nullptr;   // n_chunks entries
+    float *d_partials = nullptr;   // n_chunks * CF_WAVES floats (sqnorm scratch)
+};
+
+namespace {
+
+class DeviceGuard {
+public:
+    explicit DeviceGuard(int device) : ok_(false), prev_(0)
+    {
+        if (hipGetDevice(&prev_) != hipSuccess) return;
+        if (prev_ != device && hipSetDevice(device) != hipSuccess) return;
+        ok_ = true;
+        changed_ = prev_ != device;
+    }
+    ~DeviceGuard()
+    {
+        if (ok_ && changed_) (void)hipSetDevice(prev_);
+    }
+    bool ok() const { return ok_; }
+
+private:
+    bool ok_;
+    bool changed_ = false;
+    int prev_;
+};
+
+cf_status check_tensor(const cf_tensor &t)
+{
+    if (t.dtype != CF_F32 && t.dtype != CF_BF16) return CF_ERR_DTYPE;
+    if (t.numel != 0 && t.data == nullptr) return CF_ERR_NULL;
+    if (t.numel != 0 && (reinterpret_cast<uint64_t>(t.data) % elem_size(t.dtype)) != 0) return CF_ERR_ALIGN;
+    if (t.numel > (1ull << 40)) return CF_ERR_LIMIT;
+    return CF_OK;
+}
+
+uint64_t chunks_of(uint64_t numel, uint32_t chunk_elems) { return (numel + chunk_elems - 1) / chunk_elems; }
+
+struct Range {
+    uint64_t lo, hi;
+    uint32_t index;
+};
+
+// `out` may coincide with `in` tensor for tensor; any other shared byte is an error.
+cf_status check_pair(const cf_stage *in, const cf_stage *out)
+{
+    if (in->tensors.size() != out->tensors.size()) return CF_ERR_SHAPE_MISMATCH;
+    const size_t n = in->tensors.size();
+    for (size_t t = 0; t < n; ++t) {
+        if (in->tensors[t].numel != out->tensors[t].numel || in->tensors[t].dtype != out->tensors[t].dtype)
+            return CF_ERR_SHAPE_MISMATCH;
+    }
+    // Sweep over the input ranges sorted by address; for each output range look at its neighbours.
+    std::vector<Range> rin;
+    rin.reserve(n);
+    for (size_t t = 0; t < n; ++t) {
+        const HostTensor &h = in->tensors[t];
+        if (h.numel) rin.push_back({h.addr, h.addr + h.numel * elem_size(h.dtype), (uint32_t)t});
+    }
+    std::sort(rin.begin(), rin.end(), [](const Range &x, const Range &y) { return x.lo < y.lo; });
+    // Input ranges may themselves overlap (a tensor listed twice); keep a running maximum of `hi`.
+    std::vector<uint64_t> max_hi(rin.size());
+    uint64_t m = 0;
+    for (size_t i = 0; i < rin.size(); ++i) {
+        m = std::max(m, rin[i].hi);
+        max_hi[i] = m;
+    }
+    for (size_t t = 0; t < n; ++t) {
+        const HostTensor &o = out->tensors[t];
+        if (!o.numel) continue;
+        const uint64_t lo = o.addr, hi = o.addr + o.numel * elem_size(o.dtype);
+        // first input range with lo >= hi of the output: everything from there on is clear
+        size_t end = std::lower_bound(rin.begin(), rin.end(), hi,
+                                      [](const Range &r, uint64_t v) { return r.lo < v; }) - rin.begin();
+        for (size_t i = end; i-- > 0;) {
+            if (max_hi[i] <= lo) break;   // nothing at or before i reaches the output range
+            if (rin[i].hi > lo) {
+                const bool same = rin[i].index == t && rin[i].lo == lo && rin[i].hi == hi;
+                if (!same) return CF_ERR_ALIAS;
+            }
+        }
+    }
+    return CF_OK;
+}
+
+// Output tensors must not overlap one another either (two writers of one byte).
+cf_status check_self(const cf_stage *out)
+{
+    std::vector<Range> r;
+    for (size_t t = 0; t < out->tensors.size(); ++t) {
+        const HostTensor &h = out->tensors[t];
+        if (h.numel) r.push_back({h.addr, h.addr + h.numel * elem_size(h.dtype), (uint32_t)t});
+    }
+    std::sort(r.begin(), r.end(), [](const Range &x, const Range &y) { return x.lo < y.lo; });
+    for (size_t i = 1; i < r.size(); ++i)
+        if (r[i].lo < r[i - 1].hi) return CF_ERR_ALIAS;
+    return CF_OK;
+}
+
+cf_status checked_pair(cf_ctx *ctx, const cf_stage *in, const cf_stage *out)
+{
+    const std::pair<uint64_t, uint64_t> key(in->id, out->id);
+    if (std::find(ctx->checked.begin(), ctx->checked.end(), key) != ctx->checked.end()) return CF_OK;
+    try {
+        cf_status st = check_pair(in, out);
+        if (st != CF_OK) return st;
+        st = check_self(out);
+        if (st != CF_OK) return st;
+        if (ctx->checked.size() >= 256) ctx->checked.erase(ctx->checked.begin());
+        ctx->checked.push_back(key);
+    } catch (...) {
+        return CF_ERR_LIMIT;   // host memory exhausted
+    }
+    return CF_OK;
+}
+
+void forget_stage(cf_ctx *ctx, uint64_t id)
+{
+    auto &v = ctx->checked;
+    v.erase(std::remove_if(v.begin(), v.end(),
+                           [id](const std::pair<uint64_t, uint64_t> &p) { return p.first == id || p.second == id; }),
+            v.end());
+}
+
+uint32_t grid_for(const cf_ctx *ctx, uint32_t n_chunks, uint32_t blocks_per_cu)
+{
+    uint64_t cap = (uint64_t)ctx->num_cu * blocks_per_cu;
+    uint64_t g = std::min<uint64_t>(n_chunks, cap);
+    return (uint32_t)std::max<uint64_t>(g, 1);
+}
+
+}  // namespace
+
+extern "C" {
+
+void cf_default_tuning(cf_tuning *out)
+{
+    if (!out) return;
+    out->chunk_elems = kDefaultChunkElems;
+    out->sqnorm_blocks_per_cu = kDefaultSqnormBlocksPerCu;
+    out->blend_blocks_per_cu = kDefaultBlendBlocksPerCu;
+    out->copy_blocks_per_cu = kDefaultCopyBlocksPerCu;
+}
+
+const char *cf_status_string(cf_status status)
+{
+    switch (status) {
+    case CF_OK: return "CF_OK";
+    case CF_ERR_NULL: return "CF_ERR_NULL: required pointer is NULL";
+    case CF_ERR_SHAPE_MISMATCH: return "CF_ERR_SHAPE_MISMATCH: stages differ in tensor count, numel or dtype";
+    case CF_ERR_DTYPE: return "CF_ERR_DTYPE: unknown or unsupported element type";
+    case CF_ERR_ALIGN: return "CF_ERR_ALIGN: tensor data not aligned to its element size";
+    case CF_ERR_LIMIT: return "CF_ERR_LIMIT: size beyond what the library supports";
+    case CF_ERR_HIP: return "CF_ERR_HIP: HIP runtime call failed";
+    case CF_ERR_ALIAS: return "CF_ERR_ALIAS: output overlaps an input other than element for element";
+    case CF_ERR_CONTEXT: return "CF_ERR_CONTEXT: handles belong to different contexts";
+    default: return "unknown cf_status";
+    }
+}
+
+uint64_t cf_plan_num_chunks(const cf_tensor *tensors, uint32_t num_tensors, uint32_t chunk_elems)
+{
+    if ((num_tensors && !tensors) || chunk_elems == 0) return UINT64_MAX;
+    uint64_t n = 0;
+    for (uint32_t t = 0; t < num_tensors; ++t) n += chunks_of(tensors[t].numel, chunk_elems);
+    return n;
+}
+
+cf_status cf_plan_chunks(const cf_tensor *tensors, uint32_t num_tensors, uint32_t chunk_elems,
+                         uint32_t *chunk_tensor, uint64_t *chunk_first, uint32_t *chunk_len, uint64_t cap)
+{
+    if ((num_tensors && !tensors) || !chunk_tensor || !chunk_first || !chunk_len) return CF_ERR_NULL;
+    if (chunk_elems == 0) return CF_ERR_LIMIT;
+    uint64_t c = 0;
+    for (uint32_t t = 0; t < num_tensors; ++t) {
+        for (uint64_t first = 0; first < tensors[t].numel; first += chunk_elems) {
+            if (c >= cap) return CF_ERR_LIMIT;
+            chunk_tensor[c] = t;
+            chunk_first[c] = first;
+            chunk_len[c] = (uint32_t)std::min<uint64_t>(chunk_elems, tensors[t].numel - first);
+            ++c;
+        }
+    }
+    return CF_OK;
+}
+
+cf_status cf_ctx_create(int device, const cf_tuning *tuning, cf_ctx **out)
+{
+    if (!out) return CF_ERR_NULL;
+    *out = nullptr;
+    cf_tuning t;
+    cf_default_tuning(&t);
+    if (tuning) {
+        if (tuning->chunk_elems) t.chunk_elems = tuning->chunk_elems;
+        if (tuning->sqnorm_blocks_per_cu) t.sqnorm_blocks_per_cu = tuning->sqnorm_blocks_per_cu;
+        if (tuning->blend_blocks_per_cu) t.blend_blocks_per_cu = tuning->blend_blocks_per_cu;
+        if (tuning->copy_blocks_per_cu) t.copy_blocks_per_cu = tuning->copy_blocks_per_cu;
+    }
+    if (t.chunk_elems % kChunkElemsGranule != 0 || t.chunk_elems > kMaxChunkElems) return CF_ERR_LIMIT;
+    if (t.sqnorm_blocks_per_cu > 64 || t.blend_blocks_per_cu > 64 || t.copy_blocks_per_cu > 64) return CF_ERR_LIMIT;
+
+    int count = 0;
+    if (hipGetDeviceCount(&count) != hipSuccess || device < 0 || device >= count) return CF_ERR_HIP;
+    DeviceGuard guard(device);
+    if (!guard.ok()) return CF_ERR_HIP;
+    int num_cu = 0;
+    if (hipDeviceGetAttribute(&num_cu, hipDeviceAttributeMultiprocessorCount, device) != hipSuccess || num_cu <= 0)
+        return CF_ERR_HIP;
+    cf_ctx *ctx = new (std::nothrow) cf_ctx;
+    if (!ctx) return CF_ERR_LIMIT;
+    ctx->device = device;
+    ctx->num_cu = num_cu;
+    ctx->tuning = t;
+    void *p = nullptr;
+    if (hipMalloc(&p, kCtxWordBytes) != hipSuccess) {
+        delete ctx;
+        return CF_ERR_HIP;
+    }
+    if (hipMemset(p, 0, kCtxWordBytes) != hipSuccess || hipDeviceSynchronize() != hipSuccess) {
+        (void)hipFree(p);
+        delete ctx;
+        return CF_ERR_HIP;
+    }
+    ctx->d_words = static_cast<uint32_t *>(p);
+    *out = ctx;
+    return CF_OK;
+}
+
+cf_status cf_ctx_destroy(cf_ctx *ctx)
+{
+    if (!ctx) return CF_OK;
+    cf_status st = CF_OK;
+    {
+        DeviceGuard guard(ctx->device);
+        if (!guard.ok() || hipFree(ctx->d_words) != hipSuccess) st = CF_ERR_HIP;
+    }
+    delete ctx;
+    return st;
+}
+
+cf_status cf_stage_create(cf_ctx *ctx, const cf_tensor *tensors, uint32_t num_tensors, cf_stage **out)
+{
+    if (!ctx || !out || (num_tensors && !tensors)) return CF_ERR_NULL;
+    *out = nullptr;
+    const uint32_t chunk_elems = ctx->tuning.chunk_elems;
+    uint64_t n_chunks = 0;
+    for (uint32_t t = 0; t < num_tensors; ++t) {
+        cf_status st = check_tensor(tensors[t]);
+        if (st != CF_OK) return st;
+        n_chunks += chunks_of(tensors[t].numel, chunk_elems);
+    }
+    if (n_chunks >= kMaxChunksPerStage) return CF_ERR_LIMIT;
+
+    cf_stage *stage = new (std::nothrow) cf_stage;
+    if (!stage) return CF_ERR_LIMIT;
+    stage->ctx = ctx;
+    stage->id = g_next_stage_id.fetch_add(1);
+    stage->n_chunks = (uint32_t)n_chunks;
+    std::vector<CfChunk> table;
+    try {
+        table.reserve(n_chunks);
+        stage->tensors.reserve(num_tensors);
+    } catch (...) {
+        delete stage;
+        return CF_ERR_LIMIT;   // host memory exhausted
+    }
+    for (uint32_t t = 0; t < num_tensors; ++t) {
+        const cf_tensor &d = tensors[t];
+        HostTensor h{reinterpret_cast<uint64_t>(d.data), d.numel, d.dtype};
+        stage->tensors.push_back(h);
+        stage->numel += d.numel;
+        stage->nbytes += d.numel * elem_size(d.dtype);
+        if (d.dtype != CF_F32) stage->all_f32 = false;
+        for (uint64_t first = 0; first < d.numel; first += chunk_elems) {
+            CfChunk c;
+            c.addr = h.addr + first * elem_size(d.dtype);
+            c.len = (uint32_t)std::min<uint64_t>(chunk_elems, d.numel - first);
+            c.dtype = (uint32_t)d.dtype;
+            table.push_back(c);
+        }
+    }
+    if (n_chunks) {
+        DeviceGuard guard(ctx->device);
+        void *p = nullptr, *q = nullptr;
+        bool ok = guard.ok() && hipMalloc(&p, n_chunks * sizeof(CfChunk)) == hipSuccess;
+        ok = ok && hipMalloc(&q, n_chunks * CF_WAVES * sizeof(float)) == hipSuccess;
+        ok = ok && hipMemcpy(p, table.data(), n_chunks * sizeof(CfChunk), hipMemcpyHostToDevice) == hipSuccess;
+        ok = ok && hipMemset(q, 0, n_chunks * CF_WAVES * sizeof(float)) == hipSuccess;
+        ok = ok && hipDeviceSynchronize() == hipSuccess;
+        if (!ok) {
+            if (p) (void)hipFree(p);
+            if (q) (void)hipFree(q);
+            delete stage;
+            return CF_ERR_HIP;
+        }
+        stage->d_chunks = static_cast<CfChunk *>(p);
+        stage->d_partials = static_cast<float *>(q);
+    }
+    *out = stage;
+    return CF_OK;
+}
+
+cf_status cf_stage_destroy(cf_stage *stage)
+{
+    if (!stage) return CF_OK;
+    cf_status st = CF_OK;
+    if (stage->ctx) forget_stage(stage->ctx, stage->id);
+    if (stage->d_chunks || stage->d_partials) {
+        DeviceGuard guard(stage->ctx->device);
+        if (!guard.ok()) st = CF_ERR_HIP;
+        if (stage->d_chunks && hipFree(stage->d_chunks) != hipSuccess) st = CF_ERR_HIP;
+        if (stage->d_partials && hipFree(stage->d_partials) != hipSuccess) st = CF_ERR_HIP;
+    }
+    delete stage;
+    return st;
+}
+
+uint32_t cf_stage_num_tensors(const cf_stage *stage) { return stage ? (uint32_t)stage->tensors.size() : 0; }
+uint64_t cf_stage_numel(const cf_stage *stage) { return stage ? stage->numel : 0; }
+uint64_t cf_stage_nbytes(const cf_stage *stage) { return stage ? stage->nbytes : 0; }
+uint32_t cf_stage_num_chunks(const cf_stage *stage) { return stage ? stage->n_chunks : 0; }
+
+cf_status cf_stage_grad_sqnorm(cf_ctx *ctx, const cf_stage *const *grad_stages, uint32_t n_stages,
+                               double *d_omega_out, void *stream)
+{
+    if (!ctx || (n_stages && (!grad_stages || !d_omega_out))) return CF_ERR_NULL;
+    for (uint32_t s = 0; s < n_stages; ++s) {
+        if (!grad_stages[s]) return CF_ERR_NULL;
+        if (grad_stages[s]->ctx != ctx) return CF_ERR_CONTEXT;
+        if (!grad_stages[s]->all_f32) return CF_ERR_DTYPE;
+    }
+    DeviceGuard guard(ctx->device);
+    if (!guard.ok()) return CF_ERR_HIP;
+    for (uint32_t base = 0; base < n_stages; base += CF_MAX_SEG) {
+        CfSqnormArgs args;
+        std::memset(&args, 0, sizeof args);
+        const uint32_t n = std::min<uint32_t>(CF_MAX_SEG, n_stages - base);
+        uint64_t total = 0;
+        for (uint32_t k = 0; k < n; ++k) {
+            const cf_stage *st = grad_stages[base + k];
+            args.seg[k].chunks = st->d_chunks;
+            args.seg[k].partials = st->d_partials;
+            args.seg[k].chunk_begin = (uint32_t)total;
+            args.seg[k].n_chunks = st->n_chunks;
+            total += st->n_chunks;
+            if (total >= kMaxChunksPerStage) return CF_ERR_LIMIT;
+        }
+        args.n_seg = n;
+        args.total_chunks = (uint32_t)total;
+        args.omega_out = d_omega_out + base;
+        args.words = ctx->d_words;
+        const uint32_t grid = grid_for(ctx, args.total_chunks, ctx->tuning.sqnorm_blocks_per_cu);
+        if (cf_launch_sqnorm(args, grid, static_cast<hipStream_t>(stream)) != hipSuccess) return CF_ERR_HIP;
+    }
+    return CF_OK;
+}
+
+cf_status cf_recover_stage_weighted_avg(cf_ctx *ctx, const cf_stage *prev, const cf_stage *next,
+                                        const double *d_omega_prev, const double *d_omega_next,
+                                        cf_stage *lost, void *stream)
+{
+    if (!ctx || !prev || !next || !lost || !d_omega_prev || !d_omega_next) return CF_ERR_NULL;
+    if (prev->ctx != ctx || next->ctx != ctx || lost->ctx != ctx) return CF_ERR_CONTEXT;
+    cf_status st = checked_pair(ctx, prev, lost);
+    if (st != CF_OK) return st;
+    st = checked_pair(ctx, next, lost);
+    if (st != CF_OK) return st;
+    if (lost->n_chunks == 0) return CF_OK;
+    DeviceGuard guard(ctx->device);
+    if (!guard.ok()) return CF_ERR_HIP;
+    const uint32_t grid = grid_for(ctx, lost->n_chunks, ctx->tuning.blend_blocks_per_cu);
+    if (cf_launch_blend(prev->d_chunks, next->d_chunks, lost->d_chunks, lost->n_chunks, d_omega_prev,
+                        d_omega_next, ctx->d_words, grid, static_cast<hipStream_t>(stream)) != hipSuccess)
+        return CF_ERR_HIP;
+    return CF_OK;
+}
+
+cf_status cf_copy_stage(cf_ctx *ctx, const cf_stage *src, cf_stage *dst, void *stream)
+{
+    if (!ctx || !src || !dst) return CF_ERR_NULL;
+    if (src->ctx != ctx || dst->ctx != ctx) return CF_ERR_CONTEXT;
+    cf_status st = checked_pair(ctx, src, dst);
+    if (st != CF_OK) return st;
+    if (dst->n_chunks == 0) return CF_OK;
+    DeviceGuard guard(ctx->device);
+    if (!guard.ok()) return CF_ERR_HIP;
+    const uint32_t grid = grid_for(ctx, dst->n_chunks, ctx->tuning.copy_blocks_per_cu);
+    if (cf_launch_copy(src->d_chunks, dst->d_chunks, dst->n_chunks, grid, static_cast<hipStream_t>(stream)) !=
+        hipSuccess)
+        return CF_ERR_HIP;
+    return CF_OK;
+}
+
+cf_status cf_read_flags(cf_ctx *ctx, void *stream, uint32_t *flags, int clear)
+{
+    if (!ctx || !flags) return CF_ERR_NULL;
+    DeviceGuard guard(ctx->device);
+    if (!guard.ok()) return CF_ERR_HIP;
+    hipStream_t s = static_cast<hipStream_t>(stream);
+    if (hipStreamSynchronize(s) != hipSuccess) return CF_ERR_HIP;
+    if (hipMemcpy(flags, ctx->d_words + CF_WORD_FLAGS, sizeof(uint32_t), hipMemcpyDeviceToHost) != hipSuccess)
+        return CF_ERR_HIP;
+    if (clear) {
+        if (hipMemset(ctx->d_words + CF_WORD_FLAGS, 0, sizeof(uint32_t)) != hipSuccess) return CF_ERR_HIP;
+        if (hipDeviceSynchronize() != hipSuccess) return CF_ERR_HIP;
+    }
+    return CF_OK;
+}
+
+}  // extern "C"

@@ -1,0 +1,52 @@
+// Internal interface between the C ABI (host side) and the gfx950 kernels.
+// Not installed; the public contract is include/checkfree.h.
+#ifndef CF_KERNELS_H
+#define CF_KERNELS_H
+
+#include <hip/hip_runtime_api.h>
+#include <stdint.h>
+
+// One unit of work: a contiguous run of elements of one tensor.  A stage's
+// chunk table is an array of these in device memory, in tensor order; stages
+// that agree in numel and dtype per tensor have tables that agree in everything
+// but the addresses, so entry c of three congruent stages names the same
+// elements of corresponding tensors.
+struct CfChunk {
+    uint64_t addr;   // device address of the chunk's first element
+    uint32_t len;    // elements
+    uint32_t dtype;  // CF_F32 / CF_BF16
+};
+
+constexpr int CF_THREADS = 256;          // workgroup size of every kernel: 4 wavefronts
+constexpr int CF_WAVES = CF_THREADS / 64;
+constexpr int CF_MAX_SEG = 64;           // stages per sqnorm launch
+
+// Device word block owned by a context.
+constexpr int CF_WORD_TICKET = 0;        // workgroups finished in the running sqnorm launch
+constexpr int CF_WORD_FLAGS = 1;         // sticky CF_FLAG_* bits
+
+struct CfSqnormSeg {
+    const CfChunk *chunks;   // the stage's chunk table
+    float *partials;         // CF_WAVES slots per chunk
+    uint32_t chunk_begin;    // index of the stage's first chunk in the launch
+    uint32_t n_chunks;
+};
+
+struct CfSqnormArgs {
+    CfSqnormSeg seg[CF_MAX_SEG];
+    uint32_t n_seg;
+    uint32_t total_chunks;
+    double *omega_out;       // n_seg doubles
+    uint32_t *words;         // context word block
+};
+
+hipError_t cf_launch_sqnorm(const CfSqnormArgs &args, uint32_t grid, hipStream_t stream);
+
+hipError_t cf_launch_blend(const CfChunk *prev, const CfChunk *next, const CfChunk *lost, uint32_t n_chunks,
+                           const double *d_omega_prev, const double *d_omega_next, uint32_t *words,
+                           uint32_t grid, hipStream_t stream);
+
+hipError_t cf_launch_copy(const CfChunk *src, const CfChunk *dst, uint32_t n_chunks, uint32_t grid,
+                          hipStream_t stream);
+
+#endif

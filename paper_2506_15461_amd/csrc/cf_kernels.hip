@@ -1,0 +1,446 @@
+// gfx950 kernels of the CheckFree recovery hot path.
+//
+// All three are HBM-streaming kernels: a grid of 256-thread workgroups walks a
+// device-side chunk table (one multi-tensor launch per operation), every lane
+// moves 16 bytes per memory instruction, and there is no reuse, so nothing is
+// staged through LDS on the streaming side.  Nothing here is a contraction, so
+// no MFMA.
+//
+// Paper: "CheckFree: Memoryless Recovery" (omega = squared gradient norm of a
+// stage; the weighted-average display equation; Algorithm 1) and "CheckFree+:
+// First and Last Stage Recovery" (exact copies).
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+#include "cf_kernels.h"
+
+// Every binary64 operation of the blend is rounded on its own, as the formula
+// is written; fused multiply-adds are only the explicit ones below.
+#pragma clang fp contract(off)
+
+namespace {
+
+typedef float f32x4 __attribute__((ext_vector_type(4)));
+typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
+
+// Tensor data is always device (global) memory; saying so keeps the compiler
+// from emitting generic-address (flat) memory instructions.
+#define CF_GLOBAL __attribute__((address_space(1)))
+typedef CF_GLOBAL const float *gcf32;
+typedef CF_GLOBAL float *gf32;
+typedef CF_GLOBAL const f32x4 *gcf32x4;
+typedef CF_GLOBAL f32x4 *gf32x4;
+typedef CF_GLOBAL const u32x4 *gcu32x4;
+typedef CF_GLOBAL u32x4 *gu32x4;
+typedef CF_GLOBAL const uint16_t *gcu16;
+typedef CF_GLOBAL uint16_t *gu16;
+typedef CF_GLOBAL const uint32_t *gcu32;
+typedef CF_GLOBAL uint32_t *gu32;
+typedef CF_GLOBAL const unsigned char *gcu8;
+typedef CF_GLOBAL unsigned char *gu8;
+
+constexpr uint32_t kFlagDegenerateOmega = 1u;
+constexpr uint32_t kFlagNonfiniteOmega = 2u;
+constexpr uint32_t kDtypeF32 = 0u;
+
+// ---------------------------------------------------------------------------
+// Wavefront reduction on the DPP cross-lane path (no LDS traffic).
+// ---------------------------------------------------------------------------
+
+template <int kCtrl>
+__device__ __forceinline__ float dpp_permute(float v)
+{
+    return __int_as_float(__builtin_amdgcn_update_dpp(0, __float_as_int(v), kCtrl, 0xF, 0xF, true));
+}
+
+// Sum of v over the 64 lanes, same value in a fixed association on every run:
+// butterfly inside each row of 16 lanes (quad_perm [1,0,3,2], quad_perm
+// [2,3,0,1], row_half_mirror, row_mirror), then the four row sums as
+// (r0 + r1) + (r2 + r3).
+__device__ __forceinline__ float wave_sum(float v)
+{
+    v += dpp_permute<0xB1>(v);
+    v += dpp_permute<0x4E>(v);
+    v += dpp_permute<0x141>(v);
+    v += dpp_permute<0x140>(v);
+    float r0 = __int_as_float(__builtin_amdgcn_readlane(__float_as_int(v), 0));
+    float r1 = __int_as_float(__builtin_amdgcn_readlane(__float_as_int(v), 16));
+    float r2 = __int_as_float(__builtin_amdgcn_readlane(__float_as_int(v), 32));
+    float r3 = __int_as_float(__builtin_amdgcn_readlane(__float_as_int(v), 48));
+    return (r0 + r1) + (r2 + r3);
+}
+
+// Elements before the first 16-byte boundary at or after `addr`.
+__device__ __forceinline__ uint32_t head_elems(uint64_t addr, uint32_t elem_bytes, uint32_t len)
+{
+    uint32_t h = (uint32_t)((16u - (uint32_t)(addr & 15u)) & 15u) / elem_bytes;
+    return h < len ? h : len;
+}
+
+// ---------------------------------------------------------------------------
+// omega = ||grad W^S||^2, all stages of a launch in one grid.
+// ---------------------------------------------------------------------------
+
+// Sum of squares of this lane's share of one fp32 chunk.  Lane t of the
+// workgroup takes the 16-byte vectors t, t+256, t+512, ... of the chunk's
+// aligned body; kUnroll of them are in flight at a time.
+template <int kUnroll>
+__device__ __forceinline__ float chunk_sqsum_f32(gcf32 p, uint32_t len, uint32_t tid)
+{
+    float a0 = 0.f, a1 = 0.f, a2 = 0.f, a3 = 0.f;
+    const uint32_t head = head_elems((uint64_t)p, 4u, len);
+    if (tid < head) {
+        float v = p[tid];
+        a0 = __builtin_fmaf(v, v, a0);
+    }
+    gcf32x4 q = (gcf32x4)(p + head);
+    const uint32_t rem = len - head;
+    const uint32_t n4 = rem >> 2;
+    uint32_t i = tid;
+    for (; i + (kUnroll - 1) * CF_THREADS < n4; i += kUnroll * CF_THREADS) {
+        f32x4 v[kUnroll];
+#pragma unroll
+        for (int u = 0; u < kUnroll; ++u) v[u] = __builtin_nontemporal_load(q + i + u * CF_THREADS);
+#pragma unroll
+        for (int u = 0; u < kUnroll; ++u) {
+            a0 = __builtin_fmaf(v[u].x, v[u].x, a0);
+            a1 = __builtin_fmaf(v[u].y, v[u].y, a1);
+            a2 = __builtin_fmaf(v[u].z, v[u].z, a2);
+            a3 = __builtin_fmaf(v[u].w, v[u].w, a3);
+        }
+    }
+    for (; i < n4; i += CF_THREADS) {
+        f32x4 v = __builtin_nontemporal_load(q + i);
+        a0 = __builtin_fmaf(v.x, v.x, a0);
+        a1 = __builtin_fmaf(v.y, v.y, a1);
+        a2 = __builtin_fmaf(v.z, v.z, a2);
+        a3 = __builtin_fmaf(v.w, v.w, a3);
+    }
+    const uint32_t tail = rem & 3u;
+    if (tid < tail) {
+        float v = p[head + (n4 << 2) + tid];
+        a0 = __builtin_fmaf(v, v, a0);
+    }
+    return (a0 + a1) + (a2 + a3);
+}
+
+// Workgroup b takes chunks b, b + grid, b + 2 grid, ...  Each wavefront writes
+// the sum of squares of its lanes' share of a chunk to slot (chunk, wavefront)
+// of the owning stage's partial array, so the partials do not depend on the
+// grid size.  The last workgroup to finish (ticket) adds each stage's partials
+// in binary64 in a fixed order and writes omega.
+__global__ __launch_bounds__(CF_THREADS) void cf_sqnorm_kernel(CfSqnormArgs args)
+{
+    __shared__ double red[CF_THREADS];
+    __shared__ uint32_t s_is_last;
+
+    const uint32_t tid = threadIdx.x;
+    const uint32_t wave = tid >> 6;
+    const uint32_t lane = tid & 63u;
+
+    uint32_t s = 0;
+    for (uint32_t c = blockIdx.x; c < args.total_chunks; c += gridDim.x) {
+        while (s + 1 < args.n_seg && c >= args.seg[s + 1].chunk_begin) ++s;
+        const uint32_t local = c - args.seg[s].chunk_begin;
+        const CfChunk ch = args.seg[s].chunks[local];
+        float t = chunk_sqsum_f32<8>((gcf32)ch.addr, ch.len, tid);
+        float w = wave_sum(t);
+        if (lane == 0) args.seg[s].partials[(uint64_t)local * CF_WAVES + wave] = w;
+    }
+
+    // Publish this workgroup's partials, then take a ticket.
+    __threadfence();
+    __syncthreads();
+    if (tid == 0) {
+        uint32_t ticket = atomicAdd(&args.words[CF_WORD_TICKET], 1u);
+        s_is_last = (ticket == gridDim.x - 1u) ? 1u : 0u;
+    }
+    __syncthreads();
+    if (!s_is_last) return;
+    __threadfence();   // see every other workgroup's partials
+
+    for (uint32_t k = 0; k < args.n_seg; ++k) {
+        const float *part = args.seg[k].partials;
+        const uint64_t np = (uint64_t)args.seg[k].n_chunks * CF_WAVES;
+        double acc = 0.0;
+        for (uint64_t i = tid; i < np; i += CF_THREADS) acc += (double)part[i];
+        red[tid] = acc;
+        __syncthreads();
+        for (uint32_t off = CF_THREADS / 2; off > 0; off >>= 1) {
+            if (tid < off) red[tid] += red[tid + off];
+            __syncthreads();
+        }
+        if (tid == 0) {
+            double omega = red[0];
+            args.omega_out[k] = omega;
+            if (!(omega - omega == 0.0)) atomicOr(&args.words[CF_WORD_FLAGS], kFlagNonfiniteOmega);
+        }
+        __syncthreads();
+    }
+    if (tid == 0) args.words[CF_WORD_TICKET] = 0u;   // ready for the next launch on this context
+}
+
+// ---------------------------------------------------------------------------
+// W_lost = (w_p W_prev + w_n W_next) / (w_p + w_n)
+// ---------------------------------------------------------------------------
+
+struct BlendWeights {
+    double wp, wn, rcp;   // rcp = 1 / (wp + wn)
+};
+
+// Numerator as written, each operation rounded in binary64; then the reciprocal
+// of the denominator; one narrowing.
+__device__ __forceinline__ double blend_f64(const BlendWeights &w, double a, double b)
+{
+    double pa = w.wp * a;
+    double pb = w.wn * b;
+    double num = pa + pb;
+    return num * w.rcp;
+}
+
+__device__ __forceinline__ float blend_to_f32(const BlendWeights &w, float a, float b)
+{
+    return (float)blend_f64(w, (double)a, (double)b);
+}
+
+// binary64 -> bfloat16 bits in ONE rounding to nearest even: first to binary32
+// with round-to-odd (truncate, then make the last bit sticky), then the usual
+// nearest-even cut to the upper 16 bits.  binary32 carries more than two extra
+// bits over bfloat16, so the two steps equal a single correct rounding.
+__device__ __forceinline__ uint32_t f64_to_bf16_bits(double x)
+{
+    if (x != x) return 0x7FC0u;
+    float f = (float)x;
+    uint32_t u = __float_as_uint(f);
+    double back = (double)f;
+    if (back != x) {
+        if (__builtin_fabs(back) > __builtin_fabs(x)) u -= 1u;   // undo a round away from zero
+        u |= 1u;
+    }
+    u += 0x7FFFu + ((u >> 16) & 1u);
+    return u >> 16;
+}
+
+__device__ __forceinline__ double bf16_bits_to_f64(uint32_t h)
+{
+    return (double)__uint_as_float(h << 16);
+}
+
+__device__ __forceinline__ uint32_t blend_bf16_pair(const BlendWeights &w, uint32_t a, uint32_t b)
+{
+    uint32_t lo = f64_to_bf16_bits(blend_f64(w, bf16_bits_to_f64(a & 0xFFFFu), bf16_bits_to_f64(b & 0xFFFFu)));
+    uint32_t hi = f64_to_bf16_bits(blend_f64(w, bf16_bits_to_f64(a >> 16), bf16_bits_to_f64(b >> 16)));
+    return lo | (hi << 16);
+}
+
+template <int kUnroll>
+__device__ __forceinline__ void blend_chunk_f32(const BlendWeights &w, gcf32 pa, gcf32 pb, gf32 po, uint32_t len,
+                                                uint32_t tid)
+{
+    const uint32_t mis = (uint32_t)((uint64_t)pa & 15u);
+    if (mis != (uint32_t)((uint64_t)pb & 15u) || mis != (uint32_t)((uint64_t)po & 15u)) {
+        // The three tensors sit differently inside their 16-byte lines: dword path.
+        for (uint32_t i = tid; i < len; i += CF_THREADS) po[i] = blend_to_f32(w, pa[i], pb[i]);
+        return;
+    }
+    const uint32_t head = head_elems((uint64_t)pa, 4u, len);
+    if (tid < head) po[tid] = blend_to_f32(w, pa[tid], pb[tid]);
+    gcf32x4 qa = (gcf32x4)(pa + head);
+    gcf32x4 qb = (gcf32x4)(pb + head);
+    gf32x4 qo = (gf32x4)(po + head);
+    const uint32_t rem = len - head;
+    const uint32_t n4 = rem >> 2;
+    uint32_t i = tid;
+    for (; i + (kUnroll - 1) * CF_THREADS < n4; i += kUnroll * CF_THREADS) {
+        f32x4 a[kUnroll], b[kUnroll];
+#pragma unroll
+        for (int u = 0; u < kUnroll; ++u) {
+            a[u] = __builtin_nontemporal_load(qa + i + u * CF_THREADS);
+            b[u] = __builtin_nontemporal_load(qb + i + u * CF_THREADS);
+        }
+#pragma unroll
+        for (int u = 0; u < kUnroll; ++u) {
+            f32x4 o;
+            o.x = blend_to_f32(w, a[u].x, b[u].x);
+            o.y = blend_to_f32(w, a[u].y, b[u].y);
+            o.z = blend_to_f32(w, a[u].z, b[u].z);
+            o.w = blend_to_f32(w, a[u].w, b[u].w);
+            __builtin_nontemporal_store(o, qo + i + u * CF_THREADS);
+        }
+    }
+    for (; i < n4; i += CF_THREADS) {
+        f32x4 a = __builtin_nontemporal_load(qa + i);
+        f32x4 b = __builtin_nontemporal_load(qb + i);
+        f32x4 o;
+        o.x = blend_to_f32(w, a.x, b.x);
+        o.y = blend_to_f32(w, a.y, b.y);
+        o.z = blend_to_f32(w, a.z, b.z);
+        o.w = blend_to_f32(w, a.w, b.w);
+        __builtin_nontemporal_store(o, qo + i);
+    }
+    const uint32_t tail = rem & 3u;
+    const uint32_t tbase = head + (n4 << 2);
+    if (tid < tail) po[tbase + tid] = blend_to_f32(w, pa[tbase + tid], pb[tbase + tid]);
+}
+
+template <int kUnroll>
+__device__ __forceinline__ void blend_chunk_bf16(const BlendWeights &w, gcu16 pa, gcu16 pb, gu16 po, uint32_t len,
+                                                 uint32_t tid)
+{
+    const uint32_t mis = (uint32_t)((uint64_t)pa & 15u);
+    if (mis != (uint32_t)((uint64_t)pb & 15u) || mis != (uint32_t)((uint64_t)po & 15u)) {
+        for (uint32_t i = tid; i < len; i += CF_THREADS)
+            po[i] = (uint16_t)f64_to_bf16_bits(blend_f64(w, bf16_bits_to_f64(pa[i]), bf16_bits_to_f64(pb[i])));
+        return;
+    }
+    const uint32_t head = head_elems((uint64_t)pa, 2u, len);
+    if (tid < head)
+        po[tid] = (uint16_t)f64_to_bf16_bits(blend_f64(w, bf16_bits_to_f64(pa[tid]), bf16_bits_to_f64(pb[tid])));
+    gcu32x4 qa = (gcu32x4)(pa + head);
+    gcu32x4 qb = (gcu32x4)(pb + head);
+    gu32x4 qo = (gu32x4)(po + head);
+    const uint32_t rem = len - head;
+    const uint32_t n8 = rem >> 3;
+    uint32_t i = tid;
+    for (; i + (kUnroll - 1) * CF_THREADS < n8; i += kUnroll * CF_THREADS) {
+        u32x4 a[kUnroll], b[kUnroll];
+#pragma unroll
+        for (int u = 0; u < kUnroll; ++u) {
+            a[u] = __builtin_nontemporal_load(qa + i + u * CF_THREADS);
+            b[u] = __builtin_nontemporal_load(qb + i + u * CF_THREADS);
+        }
+#pragma unroll
+        for (int u = 0; u < kUnroll; ++u) {
+            u32x4 o;
+            o.x = blend_bf16_pair(w, a[u].x, b[u].x);
+            o.y = blend_bf16_pair(w, a[u].y, b[u].y);
+            o.z = blend_bf16_pair(w, a[u].z, b[u].z);
+            o.w = blend_bf16_pair(w, a[u].w, b[u].w);
+            __builtin_nontemporal_store(o, qo + i + u * CF_THREADS);
+        }
+    }
+    for (; i < n8; i += CF_THREADS) {
+        u32x4 a = __builtin_nontemporal_load(qa + i);
+        u32x4 b = __builtin_nontemporal_load(qb + i);
+        u32x4 o;
+        o.x = blend_bf16_pair(w, a.x, b.x);
+        o.y = blend_bf16_pair(w, a.y, b.y);
+        o.z = blend_bf16_pair(w, a.z, b.z);
+        o.w = blend_bf16_pair(w, a.w, b.w);
+        __builtin_nontemporal_store(o, qo + i);
+    }
+    const uint32_t tail = rem & 7u;
+    const uint32_t tbase = head + (n8 << 3);
+    if (tid < tail) {
+        const uint32_t k = tbase + tid;
+        po[k] = (uint16_t)f64_to_bf16_bits(blend_f64(w, bf16_bits_to_f64(pa[k]), bf16_bits_to_f64(pb[k])));
+    }
+}
+
+// The norm-to-weight scaling is the kernel's prologue: every workgroup reads the
+// two binary64 omegas from device memory and derives identical weights.
+__global__ __launch_bounds__(CF_THREADS) void cf_blend_kernel(const CfChunk *prev, const CfChunk *next,
+                                                              const CfChunk *lost, uint32_t n_chunks,
+                                                              const double *d_omega_prev,
+                                                              const double *d_omega_next, uint32_t *words)
+{
+    const uint32_t tid = threadIdx.x;
+    BlendWeights w;
+    w.wp = *d_omega_prev;
+    w.wn = *d_omega_next;
+    double den = w.wp + w.wn;
+    // Usable pair: both finite and non-negative, sum a positive normal number.
+    const bool usable = (w.wp - w.wp == 0.0) && (w.wn - w.wn == 0.0) && w.wp >= 0.0 && w.wn >= 0.0 &&
+                        (den - den == 0.0) && den >= 2.2250738585072014e-308;
+    if (!usable) {
+        w.wp = 1.0;
+        w.wn = 1.0;
+        den = 2.0;
+        if (blockIdx.x == 0 && tid == 0) atomicOr(&words[CF_WORD_FLAGS], kFlagDegenerateOmega);
+    }
+    w.rcp = 1.0 / den;
+
+    for (uint32_t c = blockIdx.x; c < n_chunks; c += gridDim.x) {
+        const CfChunk ca = prev[c];
+        const CfChunk cb = next[c];
+        const CfChunk co = lost[c];
+        if (co.dtype == kDtypeF32)
+            blend_chunk_f32<4>(w, (gcf32)ca.addr, (gcf32)cb.addr, (gf32)co.addr, co.len, tid);
+        else
+            blend_chunk_bf16<4>(w, (gcu16)ca.addr, (gcu16)cb.addr, (gu16)co.addr, co.len, tid);
+    }
+}
+
+// ---------------------------------------------------------------------------
+// Bit-exact multi-tensor copy (CheckFree+).
+// ---------------------------------------------------------------------------
+
+template <int kUnroll>
+__global__ __launch_bounds__(CF_THREADS) void cf_copy_kernel(const CfChunk *src, const CfChunk *dst,
+                                                             uint32_t n_chunks)
+{
+    const uint32_t tid = threadIdx.x;
+    for (uint32_t c = blockIdx.x; c < n_chunks; c += gridDim.x) {
+        const CfChunk cs = src[c];
+        const CfChunk cd = dst[c];
+        const uint32_t esize = (cs.dtype == kDtypeF32) ? 4u : 2u;
+        const uint32_t nbytes = cs.len * esize;
+        gcu8 ps = (gcu8)cs.addr;
+        gu8 pd = (gu8)cd.addr;
+        if (((uint64_t)ps & 15u) != ((uint64_t)pd & 15u)) {
+            // Different position inside a 16-byte line: move whole elements.
+            if (esize == 4u) {
+                gcu32 s4 = (gcu32)ps;
+                gu32 d4 = (gu32)pd;
+                for (uint32_t i = tid; i < cs.len; i += CF_THREADS) d4[i] = s4[i];
+            } else {
+                gcu16 s2 = (gcu16)ps;
+                gu16 d2 = (gu16)pd;
+                for (uint32_t i = tid; i < cs.len; i += CF_THREADS) d2[i] = s2[i];
+            }
+            continue;
+        }
+        const uint32_t head = head_elems((uint64_t)ps, 1u, nbytes);
+        if (tid < head) pd[tid] = ps[tid];
+        gcu32x4 qs = (gcu32x4)(ps + head);
+        gu32x4 qd = (gu32x4)(pd + head);
+        const uint32_t rem = nbytes - head;
+        const uint32_t n16 = rem >> 4;
+        uint32_t i = tid;
+        for (; i + (kUnroll - 1) * CF_THREADS < n16; i += kUnroll * CF_THREADS) {
+            u32x4 v[kUnroll];
+#pragma unroll
+            for (int u = 0; u < kUnroll; ++u) v[u] = __builtin_nontemporal_load(qs + i + u * CF_THREADS);
+#pragma unroll
+            for (int u = 0; u < kUnroll; ++u) __builtin_nontemporal_store(v[u], qd + i + u * CF_THREADS);
+        }
+        for (; i < n16; i += CF_THREADS) __builtin_nontemporal_store(__builtin_nontemporal_load(qs + i), qd + i);
+        const uint32_t tail = rem & 15u;
+        const uint32_t tbase = head + (n16 << 4);
+        if (tid < tail) pd[tbase + tid] = ps[tbase + tid];
+    }
+}
+
+}  // namespace
+
+hipError_t cf_launch_sqnorm(const CfSqnormArgs &args, uint32_t grid, hipStream_t stream)
+{
+    hipLaunchKernelGGL(cf_sqnorm_kernel, dim3(grid), dim3(CF_THREADS), 0, stream, args);
+    return hipGetLastError();
+}
+
+hipError_t cf_launch_blend(const CfChunk *prev, const CfChunk *next, const CfChunk *lost, uint32_t n_chunks,
+                           const double *d_omega_prev, const double *d_omega_next, uint32_t *words,
+                           uint32_t grid, hipStream_t stream)
+{
+    hipLaunchKernelGGL(cf_blend_kernel, dim3(grid), dim3(CF_THREADS), 0, stream, prev, next, lost, n_chunks,
+                       d_omega_prev, d_omega_next, words);
+    return hipGetLastError();
+}
+
+hipError_t cf_launch_copy(const CfChunk *src, const CfChunk *dst, uint32_t n_chunks, uint32_t grid,
+                          hipStream_t stream)
+{
+    hipLaunchKernelGGL(cf_copy_kernel<8>, dim3(grid), dim3(CF_THREADS), 0, stream, src, dst, n_chunks);
+    return hipGetLastError();
+}

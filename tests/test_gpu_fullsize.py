@@ -1,0 +1,75 @@
+"""GPU parity at the full sizes of the five workloads, in the launch
+configuration the benchmark times (default tuning), every element compared."""
+import numpy as np
+import pytest
+import torch
+
+import oracle
+import paper_2506_15461_amd as cf
+import workloads
+from test_gpu_parity import (NORM_RTOL, ORACLE_THREADS, assert_blend_close, check_recovery, np_stage)
+
+pytestmark = pytest.mark.gpu
+
+
+@pytest.fixture(scope="module")
+def dev():
+    return torch.device("cuda", 0)
+
+
+@pytest.fixture()
+def ctx():
+    c = cf.Context(0)
+    yield c
+    torch.cuda.synchronize()
+    assert c.read_flags() == 0
+
+
+@pytest.mark.parametrize("config", [1, 2, 3])
+def test_full_recovery(ctx, dev, config):
+    print(f"workload {config}: {workloads.SPECS[config].name}", flush=True)
+    wl = workloads.make_workload(config, device=dev)
+    omega, worst = check_recovery(ctx, wl, 0, 1, 2)
+    # gross-error band from the drawing recipe: E[omega] = sum n_t sigma_t^2
+    n = np.array([np.prod(s) for s in wl.spec.shape.tensor_shapes()], dtype=np.float64)
+    for k, s in enumerate((0, 2)):
+        mean = float(np.sum(n * wl.sigmas[s] ** 2))
+        sd = float(np.sqrt(np.sum(2 * n * wl.sigmas[s] ** 4)))
+        assert abs(omega[k] - mean) < 6 * sd + 1e-5 * mean
+    print(f"  omega={omega.tolist()} blend max ulp={worst}", flush=True)
+
+
+def test_checkfree_plus_copy_full(ctx, dev):
+    wl = workloads.make_workload(4, device=dev, with_grads=False)
+    src = wl.weights[0] + wl.extra                     # the stage, E, E^-1, final norm
+    assert len(src) == 39 and sum(t.numel() for t in src) == 336_611_328
+    dst = [torch.full_like(t, float("nan")) for t in src]
+    cf.cf_copy_stage(ctx, cf.Stage(ctx, src), cf.Stage(ctx, dst))
+    torch.cuda.synchronize()
+    for s, d in zip(src, dst):
+        assert torch.equal(s.view(torch.int32), d.view(torch.int32))
+    # and against the oracle on the largest and the smallest tensor
+    for k in (36, 38, 8):
+        want = oracle.copy_stage([workloads.to_numpy(src[k])], ORACLE_THREADS)[0]
+        assert workloads.to_numpy(dst[k]).tobytes() == want.tobytes()
+
+
+def test_pipeline_norm_tracking_then_recovery(ctx, dev):
+    wl = workloads.make_workload(5, device=dev)
+    lost = wl.lost
+    assert 1 <= lost <= 6
+    print(f"pipeline workload: lost stage {lost}", flush=True)
+    grads = [cf.Stage(ctx, g) for g in wl.grads]
+    omega = cf.cf_stage_grad_sqnorm(ctx, grads)                    # all 8 stages, one launch
+    for t in wl.weights[lost]:
+        t.fill_(float("nan"))
+    prev, nxt, out = (cf.Stage(ctx, wl.weights[i]) for i in (lost - 1, lost + 1, lost))
+    cf.cf_recover_stage_weighted_avg(ctx, prev, nxt, omega[lost - 1:lost], omega[lost + 1:lost + 2], out)
+    torch.cuda.synchronize()
+    w = omega.cpu().numpy()
+    for s in range(8):
+        ref = oracle.stage_grad_sqnorm(np_stage(wl.grads[s]), ORACLE_THREADS)
+        assert abs(w[s] - ref) <= NORM_RTOL * ref, (s, w[s], ref)
+    want = oracle.recover_stage_weighted_avg(np_stage(wl.weights[lost - 1]), np_stage(wl.weights[lost + 1]),
+                                             float(w[lost - 1]), float(w[lost + 1]), ORACLE_THREADS)
+    assert_blend_close(np_stage(wl.weights[lost]), want)

@@ -1,0 +1,354 @@
+"""GPU parity: the HIP path, called through the C ABI, against the CPU oracle on
+the same seeded inputs.
+
+Bars: stage squared norms within 1e-5 relative; fp32 blended weights within
+2 ulp; bf16 blended weights within 1 bf16 ulp; copies bit-exact.  The blend is
+compared with the oracle evaluated at the omegas the GPU produced (the two bars
+cannot both hold end to end: a 1e-5 relative change of omega moves most blended
+elements by far more than 2 ulp); the norms are compared with the oracle's own
+omega separately.
+"""
+import ctypes
+
+import numpy as np
+import pytest
+import torch
+
+import exactmath as em
+import oracle
+import paper_2506_15461_amd as cf
+import workloads
+
+pytestmark = pytest.mark.gpu
+
+NORM_RTOL = 1e-5
+F32_ULP = 2
+BF16_ULP = 1
+ORACLE_THREADS = 16
+
+
+@pytest.fixture(scope="module")
+def dev():
+    return torch.device("cuda", 0)
+
+
+@pytest.fixture(scope="module")
+def ctx():
+    c = cf.Context(0)
+    yield c
+    torch.cuda.synchronize()
+    assert c.read_flags(clear=True) in (0, 1, 2, 3)
+
+
+def np_stage(stage):
+    return workloads.stage_to_numpy(stage)
+
+
+def assert_blend_close(got_stage, want_stage):
+    worst = 0
+    for t, (g, w) in enumerate(zip(got_stage, want_stage)):
+        d = em.ulp_distance(g.reshape(-1), w.reshape(-1))
+        bar = F32_ULP if g.dtype == np.float32 else BF16_ULP
+        m = int(d.max()) if d.size else 0
+        assert m <= bar, f"tensor {t}: {m} ulp (bar {bar}), {int((d > bar).sum())} elements off"
+        worst = max(worst, m)
+    return worst
+
+
+def run_recovery(ctx, weights_prev, weights_next, weights_lost, grads_prev, grads_next):
+    """The whole hot path: both norms in one launch, then the blend."""
+    prev, nxt, lost = cf.Stage(ctx, weights_prev), cf.Stage(ctx, weights_next), cf.Stage(ctx, weights_lost)
+    gp, gn = cf.Stage(ctx, grads_prev), cf.Stage(ctx, grads_next)
+    omega = cf.cf_stage_grad_sqnorm(ctx, [gp, gn])
+    cf.cf_recover_stage_weighted_avg(ctx, prev, nxt, omega[0:1], omega[1:2], lost)
+    torch.cuda.synchronize()
+    return omega.cpu().numpy()
+
+
+def check_recovery(ctx, wl, prev_i, lost_i, next_i):
+    for t in wl.weights[lost_i]:
+        t.fill_(float("nan"))                      # the lost stage's content is gone
+    omega = run_recovery(ctx, wl.weights[prev_i], wl.weights[next_i], wl.weights[lost_i],
+                         wl.grads[prev_i], wl.grads[next_i])
+    for k, s in enumerate((prev_i, next_i)):
+        ref = oracle.stage_grad_sqnorm(np_stage(wl.grads[s]), ORACLE_THREADS)
+        assert abs(omega[k] - ref) <= NORM_RTOL * ref, (s, omega[k], ref)
+    want = oracle.recover_stage_weighted_avg(np_stage(wl.weights[prev_i]), np_stage(wl.weights[next_i]),
+                                             float(omega[0]), float(omega[1]), ORACLE_THREADS)
+    return omega, assert_blend_close(np_stage(wl.weights[lost_i]), want)
+
+
+# ----------------------------------------------------------------------------
+# squared norms
+# ----------------------------------------------------------------------------
+
+def test_sqnorm_ragged_stage_and_empty_stages(ctx, dev):
+    gen = torch.Generator(device=dev).manual_seed(7)
+    shapes = workloads.ragged_shapes(1)
+    stages = []
+    for s in range(3):
+        sig = workloads.draw_sigmas(len(shapes), np.random.default_rng(s))
+        stages.append(workloads.draw_grads(shapes, sig, gen, dev))
+    stages.insert(1, [])                                            # a stage with no tensors
+    stages.append([torch.empty(0, device=dev), torch.ones(3, device=dev)])
+    handles = [cf.Stage(ctx, g) for g in stages]
+    omega = cf.cf_stage_grad_sqnorm(ctx, handles).cpu().numpy()
+    for k, g in enumerate(stages):
+        ref = oracle.stage_grad_sqnorm(np_stage(g))
+        assert abs(omega[k] - ref) <= NORM_RTOL * ref, (k, omega[k], ref)
+    assert omega[1] == 0.0 and omega[4] == 3.0
+
+
+def test_sqnorm_closed_forms(ctx, dev):
+    n = 100_003
+    c = torch.full((n,), 2.0 ** -7, device=dev)
+    ramp = torch.arange(1, 2049, device=dev, dtype=torch.float32)
+    omega = cf.cf_stage_grad_sqnorm(ctx, [cf.Stage(ctx, [c]), cf.Stage(ctx, [ramp])]).cpu().numpy()
+    assert omega[0] == n * 2.0 ** -14                     # every partial sum is exact in fp32
+    m = 2048
+    assert abs(omega[1] - m * (m + 1) * (2 * m + 1) / 6) <= NORM_RTOL * omega[1]
+
+
+def test_sqnorm_is_bitwise_reproducible_and_launch_shape_independent(dev):
+    wl = workloads.make_workload(1, device=dev, shape=workloads.StageShape(192, 512, 2))
+    results = []
+    for tuning in ({}, {"sqnorm_blocks_per_cu": 1}, {"sqnorm_blocks_per_cu": 3}):
+        c = cf.Context(0, **tuning)
+        handles = [cf.Stage(c, g) for g in wl.grads]
+        for rep in range(3):
+            results.append(cf.cf_stage_grad_sqnorm(c, handles).cpu().numpy().tobytes())
+    assert len(set(results)) == 1
+
+
+def test_sqnorm_misaligned_views(ctx, dev):
+    gen = torch.Generator(device=dev).manual_seed(9)
+    base = torch.empty(200_000, device=dev).normal_(0, 1e-3, generator=gen)
+    views = [base[1:70_001], base[70_002:70_003], base[70_003:140_010], base[140_011:199_999]]
+    omega = cf.cf_stage_grad_sqnorm(ctx, [cf.Stage(ctx, views)]).cpu().numpy()
+    ref = oracle.stage_grad_sqnorm(np_stage(views))
+    assert abs(omega[0] - ref) <= NORM_RTOL * ref
+
+
+def test_sqnorm_nonfinite_raises_flag(dev):
+    c = cf.Context(0)
+    g = torch.ones(5000, device=dev)
+    g[1234] = float("inf")
+    omega = cf.cf_stage_grad_sqnorm(c, [cf.Stage(c, [g]), cf.Stage(c, [torch.ones(10, device=dev)])]).cpu().numpy()
+    assert np.isinf(omega[0]) and omega[1] == 10.0
+    assert c.read_flags(clear=True) & cf.CF_FLAG_NONFINITE_OMEGA
+    assert c.read_flags() == 0
+
+
+def test_sqnorm_more_stages_than_one_launch_holds(ctx, dev):
+    stages = [[torch.full((k + 1,), 2.0, device=dev)] for k in range(70)]
+    omega = cf.cf_stage_grad_sqnorm(ctx, [cf.Stage(ctx, s) for s in stages]).cpu().numpy()
+    assert np.array_equal(omega, 4.0 * np.arange(1, 71))
+
+
+def test_sqnorm_rejects_bf16_gradients(ctx, dev):
+    st = cf.Stage(ctx, [torch.ones(8, device=dev, dtype=torch.bfloat16)])
+    with pytest.raises(cf.CheckFreeError) as e:
+        cf.cf_stage_grad_sqnorm(ctx, [st])
+    assert e.value.status == cf.CF_ERR_DTYPE
+
+
+# ----------------------------------------------------------------------------
+# weighted-average recovery
+# ----------------------------------------------------------------------------
+
+def _omega(dev, wp, wn):
+    return torch.tensor([wp, wn], dtype=torch.float64, device=dev)
+
+
+def _draw_pair(dev, shapes, dtype, seed):
+    gen = torch.Generator(device=dev).manual_seed(seed)
+    return (workloads.draw_weights(shapes, dtype, gen, dev), workloads.draw_weights(shapes, dtype, gen, dev))
+
+
+@pytest.mark.parametrize("dtype", ["f32", "bf16"])
+def test_blend_ragged_stage(ctx, dev, dtype):
+    shapes = workloads.ragged_shapes(2)
+    a, b = _draw_pair(dev, shapes, dtype, 21)
+    out = [torch.full_like(t, float("nan")) for t in a]
+    for wp, wn in [(3.7e-3, 1.9e-2), (1.0, 1e-9), (5e-11, 7e-4), (123.0, 123.0)]:
+        w = _omega(dev, wp, wn)
+        cf.cf_recover_stage_weighted_avg(ctx, cf.Stage(ctx, a), cf.Stage(ctx, b), w[0:1], w[1:2], cf.Stage(ctx, out))
+        torch.cuda.synchronize()
+        want = oracle.recover_stage_weighted_avg(np_stage(a), np_stage(b), wp, wn)
+        assert_blend_close(np_stage(out), want)
+
+
+@pytest.mark.parametrize("dtype", ["f32", "bf16"])
+def test_blend_special_cases_are_exact(ctx, dev, dtype):
+    shapes = workloads.ragged_shapes(3)
+    a, b = _draw_pair(dev, shapes, dtype, 22)
+    out = [torch.full_like(t, float("nan")) for t in a]
+    sa, sb, so = cf.Stage(ctx, a), cf.Stage(ctx, b), cf.Stage(ctx, out)
+    bits = torch.int32 if dtype == "f32" else torch.int16
+
+    def same(x, y):
+        return all(torch.equal(p.view(bits), q.view(bits)) for p, q in zip(x, y))
+
+    w = _omega(dev, 3.7e-3, 0.0)                     # omega_{i+1} = 0: copy of the previous stage
+    cf.cf_recover_stage_weighted_avg(ctx, sa, sb, w[0:1], w[1:2], so)
+    assert same(out, a)
+    w = _omega(dev, 0.0, 2.5)
+    cf.cf_recover_stage_weighted_avg(ctx, sa, sb, w[0:1], w[1:2], so)
+    assert same(out, b)
+    w = _omega(dev, 3.7e-3, 1.9e-2)                  # identical neighbours give back that stage
+    cf.cf_recover_stage_weighted_avg(ctx, sa, sa, w[0:1], w[1:2], so)
+    assert same(out, a)
+
+
+def test_blend_misaligned_and_in_place(ctx, dev):
+    gen = torch.Generator(device=dev).manual_seed(23)
+    n = 150_001
+    A = torch.empty(n + 8, device=dev).normal_(0, 0.02, generator=gen)
+    B = torch.empty(n + 8, device=dev).normal_(0, 0.02, generator=gen)
+    O = torch.full((n + 8,), float("nan"), device=dev)
+    w = _omega(dev, 3.7e-3, 1.9e-2)
+    for oa, ob, oo in [(1, 1, 1), (3, 3, 3), (1, 2, 3), (0, 0, 2)]:
+        a, b, o = A[oa:oa + n], B[ob:ob + n], O[oo:oo + n]
+        O.fill_(float("nan"))
+        cf.cf_recover_stage_weighted_avg(ctx, cf.Stage(ctx, [a]), cf.Stage(ctx, [b]), w[0:1], w[1:2], cf.Stage(ctx, [o]))
+        torch.cuda.synchronize()
+        want = oracle.recover_stage_weighted_avg(np_stage([a]), np_stage([b]), 3.7e-3, 1.9e-2)
+        assert_blend_close(np_stage([o]), want)
+        assert torch.isnan(O[:oo]).all() and torch.isnan(O[oo + n:]).all()      # nothing outside the tensor
+    # in place: the lost stage's memory is the previous stage's
+    a, b = A[:n].clone(), B[:n].clone()
+    want = oracle.recover_stage_weighted_avg(np_stage([a]), np_stage([b]), 3.7e-3, 1.9e-2)
+    sa = cf.Stage(ctx, [a])
+    cf.cf_recover_stage_weighted_avg(ctx, sa, cf.Stage(ctx, [b]), w[0:1], w[1:2], sa)
+    torch.cuda.synchronize()
+    assert_blend_close(np_stage([a]), want)
+
+
+@pytest.mark.parametrize("dtype", ["f32", "bf16"])
+def test_blend_subnormals_extremes_and_nonfinite_weights(ctx, dev, dtype):
+    if dtype == "f32":
+        vals_a = [2.0 ** -149, -2.0 ** -140, 3.4028234663852886e38, 0.0, -0.0, float("nan"), float("inf"), 1.0,
+                  2.0 ** -126, 1e-41, -3e-39]
+        vals_b = [2.0 ** -149, 2.0 ** -140, 3.4028234663852886e38, -0.0, -0.0, 1.0, 1.0, float("-inf"),
+                  2.0 ** -127, -2e-41, 1e-39]
+        a = torch.tensor(vals_a, dtype=torch.float32, device=dev)
+        b = torch.tensor(vals_b, dtype=torch.float32, device=dev)
+    else:
+        # every bf16 bit pattern against a shuffled copy of the same set
+        allbits = torch.arange(65536, dtype=torch.int32, device=dev).to(torch.int16)
+        perm = torch.randperm(65536, generator=torch.Generator(device=dev).manual_seed(5), device=dev)
+        a = allbits.view(torch.bfloat16)
+        b = allbits[perm].contiguous().view(torch.bfloat16)
+    out = torch.zeros_like(a)
+    for wp, wn in [(1.0, 1.0), (3.7e-3, 1.9e-2), (1.0, 3.0)]:
+        w = _omega(dev, wp, wn)
+        cf.cf_recover_stage_weighted_avg(ctx, cf.Stage(ctx, [a]), cf.Stage(ctx, [b]), w[0:1], w[1:2], cf.Stage(ctx, [out]))
+        torch.cuda.synchronize()
+        want = oracle.recover_stage_weighted_avg(np_stage([a]), np_stage([b]), wp, wn)
+        assert_blend_close(np_stage([out]), want)
+    if dtype == "f32":
+        w = _omega(dev, 1.0, 1.0)
+        cf.cf_recover_stage_weighted_avg(ctx, cf.Stage(ctx, [a]), cf.Stage(ctx, [b]), w[0:1], w[1:2], cf.Stage(ctx, [out]))
+        o = out.cpu().numpy()
+        assert o[0] == np.float32(2.0 ** -149) and o[8] != 0        # subnormal results are kept
+
+
+@pytest.mark.parametrize("wp,wn", [(0.0, 0.0), (float("nan"), 1.0), (1.0, float("inf")), (-1.0, 2.0),
+                                   (1e-320, 1e-320), (1e308, 1e308)])
+def test_blend_degenerate_omega_falls_back_to_uniform_average(dev, wp, wn):
+    c = cf.Context(0)
+    a, b = _draw_pair(dev, workloads.ragged_shapes(4, 6), "f32", 24)
+    out = [torch.full_like(t, float("nan")) for t in a]
+    w = _omega(dev, wp, wn)
+    cf.cf_recover_stage_weighted_avg(c, cf.Stage(c, a), cf.Stage(c, b), w[0:1], w[1:2], cf.Stage(c, out))
+    torch.cuda.synchronize()
+    want = oracle.recover_stage_weighted_avg(np_stage(a), np_stage(b), wp, wn)
+    assert_blend_close(np_stage(out), want)
+    assert c.read_flags(clear=True) == cf.CF_FLAG_DEGENERATE_OMEGA
+    w = _omega(dev, 1.0, 2.0)
+    cf.cf_recover_stage_weighted_avg(c, cf.Stage(c, a), cf.Stage(c, b), w[0:1], w[1:2], cf.Stage(c, out))
+    assert c.read_flags() == 0
+
+
+def test_blend_argument_errors(ctx, dev):
+    a = [torch.zeros(100, device=dev), torch.zeros(7, device=dev)]
+    b = [torch.zeros(100, device=dev), torch.zeros(7, device=dev)]
+    w = _omega(dev, 1.0, 1.0)
+    sa, sb = cf.Stage(ctx, a), cf.Stage(ctx, b)
+    cases = [
+        ([torch.zeros(100, device=dev), torch.zeros(8, device=dev)], cf.CF_ERR_SHAPE_MISMATCH),
+        ([torch.zeros(100, device=dev)], cf.CF_ERR_SHAPE_MISMATCH),
+        ([torch.zeros(100, device=dev), torch.zeros(7, device=dev, dtype=torch.bfloat16)], cf.CF_ERR_SHAPE_MISMATCH),
+    ]
+    for out, code in cases:
+        with pytest.raises(cf.CheckFreeError) as e:
+            cf.cf_recover_stage_weighted_avg(ctx, sa, sb, w[0:1], w[1:2], cf.Stage(ctx, out))
+        assert e.value.status == code
+    big = torch.zeros(300, device=dev)
+    with pytest.raises(cf.CheckFreeError) as e:          # output overlaps an input, shifted
+        cf.cf_recover_stage_weighted_avg(ctx, cf.Stage(ctx, [big[0:100]]), cf.Stage(ctx, [big[200:300]]),
+                                         w[0:1], w[1:2], cf.Stage(ctx, [big[50:150]]))
+    assert e.value.status == cf.CF_ERR_ALIAS
+    with pytest.raises(cf.CheckFreeError) as e:          # output tensors overlap one another
+        cf.cf_recover_stage_weighted_avg(ctx, sa, sb, w[0:1], w[1:2], cf.Stage(ctx, [big[0:100], big[98:105]]))
+    assert e.value.status == cf.CF_ERR_ALIAS
+    other = cf.Context(0)
+    with pytest.raises(cf.CheckFreeError) as e:
+        cf.cf_recover_stage_weighted_avg(other, sa, sb, w[0:1], w[1:2], sa)
+    assert e.value.status == cf.CF_ERR_CONTEXT
+    with pytest.raises(cf.CheckFreeError) as e:
+        cf.Stage(ctx, [torch.zeros(4, device=dev, dtype=torch.float16)])
+    assert e.value.status == cf.CF_ERR_DTYPE
+
+
+# ----------------------------------------------------------------------------
+# CheckFree+ copy
+# ----------------------------------------------------------------------------
+
+def test_copy_bit_exact_with_guard_bands(ctx, dev):
+    gen = torch.Generator(device=dev).manual_seed(31)
+    n = 200_003
+    raw = torch.randint(-2 ** 31, 2 ** 31 - 1, (n,), dtype=torch.int32, device=dev, generator=gen)
+    raw[:6] = torch.tensor([0x7FC00001, -0x3EDCBB, 0x7F800001, -2 ** 31, 1, -0x7F800001], dtype=torch.int32)
+    src = raw.view(torch.float32)
+    half = torch.randint(-2 ** 15, 2 ** 15 - 1, (4099,), dtype=torch.int16, device=dev, generator=gen).view(torch.bfloat16)
+    for so, do in [(0, 0), (1, 1), (1, 3), (2, 0)]:
+        D = torch.full((n + 16,), float("nan"), device=dev)
+        DH = torch.zeros(4099 + 16, dtype=torch.bfloat16, device=dev)
+        s = [src[so:], half[so:], torch.empty(0, device=dev)]
+        d = [D[do:do + n - so], DH[do:do + 4099 - so], torch.empty(0, device=dev)]
+        before = D.clone()
+        cf.cf_copy_stage(ctx, cf.Stage(ctx, s), cf.Stage(ctx, d))
+        torch.cuda.synchronize()
+        want = oracle.copy_stage(np_stage(s))
+        for g, wnt in zip(np_stage(d), want):
+            assert g.tobytes() == wnt.tobytes()
+        assert torch.equal(D[:do].view(torch.int32), before[:do].view(torch.int32))
+        assert torch.equal(D[do + n - so:].view(torch.int32), before[do + n - so:].view(torch.int32))
+        assert (DH[:do] == 0).all() and (DH[do + 4099 - so:] == 0).all()
+
+
+def test_copy_argument_errors(ctx, dev):
+    a = torch.zeros(300, device=dev)
+    with pytest.raises(cf.CheckFreeError) as e:
+        cf.cf_copy_stage(ctx, cf.Stage(ctx, [a[:100]]), cf.Stage(ctx, [a[50:150]]))
+    assert e.value.status == cf.CF_ERR_ALIAS
+    with pytest.raises(cf.CheckFreeError) as e:
+        cf.cf_copy_stage(ctx, cf.Stage(ctx, [a[:100]]), cf.Stage(ctx, [a[100:201]]))
+    assert e.value.status == cf.CF_ERR_SHAPE_MISMATCH
+    s = cf.Stage(ctx, [a[:100]])
+    cf.cf_copy_stage(ctx, s, s)                      # identical memory: allowed, a no-op in effect
+
+
+# ----------------------------------------------------------------------------
+# the five workloads: reduced shapes here, full shapes in test_gpu_fullsize.py
+# ----------------------------------------------------------------------------
+
+@pytest.mark.parametrize("config,shape", [
+    (1, workloads.StageShape(192, 512, 2)),
+    (2, workloads.StageShape(256, 704, 4)),
+    (3, workloads.StageShape(256, 704, 4)),
+])
+def test_recovery_reduced_shapes(ctx, dev, config, shape):
+    wl = workloads.make_workload(config, device=dev, shape=shape)
+    check_recovery(ctx, wl, 0, 1, 2)
