@@ -1,0 +1,217 @@
+#!/usr/bin/env python3
+"""Benchmark of the CheckFree recovery hot path on one MI355X.
+
+A *step* is one pass of the whole path over one synthetic workload: squared
+gradient norms of the neighbouring stages in one launch, then the fused
+norm-to-weight scaling + weighted-average blend into the lost stage (workloads
+1, 2, 3, 5), or the CheckFree+ copy (workload 4).  Inputs are resident in HBM
+before the timed region.  Prints ONE JSON line.
+
+    python bench.py [--gpus 1] [--steps K] [--warmup W] [--config 1..5] [--no-cpu-baseline]
+"""
+import argparse
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+if ROOT not in sys.path:
+    sys.path.insert(0, ROOT)
+
+HBM_PEAK_GBPS = 8000.0          # MI355X HBM3E, vendor figure
+
+
+def parse():
+    p = argparse.ArgumentParser()
+    p.add_argument("--gpus", type=int, default=1)
+    p.add_argument("--steps", type=int, default=200)
+    p.add_argument("--warmup", type=int, default=20)
+    p.add_argument("--config", type=int, default=3, help="workload 1..5 (3 = the 1.5B-shape stage the metric is quoted on)")
+    p.add_argument("--no-cpu-baseline", action="store_true")
+    p.add_argument("--cpu-seconds", type=float, default=15.0, help="target CPU time of the oracle baseline")
+    return p.parse_args()
+
+
+def main():
+    args = parse()
+    if args.gpus != 1:
+        print(f"bench.py: this build runs on exactly one GPU (asked for {args.gpus}); "
+              "the path has no multi-GPU leg.", file=sys.stderr)
+        return 2
+
+    import numpy as np
+    import torch
+
+    import paper_2506_15461_amd as cf
+    import workloads
+
+    if not torch.cuda.is_available():
+        print("bench.py: no GPU visible", file=sys.stderr)
+        return 2
+    cf.load_library()                      # fails loudly if the HIP library is not built
+    dev = torch.device("cuda", 0)
+    torch.cuda.set_device(dev)
+    spec = workloads.SPECS[args.config]
+    wl = workloads.make_workload(args.config, device=dev, with_grads=args.config != 4)
+    ctx = cf.Context(0)
+    stream = torch.cuda.current_stream()
+
+    numel = spec.shape.numel()
+    wbytes = 2 if spec.param_dtype == "bf16" else 4
+
+    if args.config == 4:
+        src_t = wl.weights[0] + wl.extra
+        dst_t = [torch.full_like(t, float("nan")) for t in src_t]
+        src, dst = cf.Stage(ctx, src_t), cf.Stage(ctx, dst_t)
+        copy_bytes = 2 * src.nbytes
+        step_bytes = copy_bytes
+        kernels = ["copy"]
+
+        def step(ev=None):
+            if ev:
+                ev[0].record(stream)
+            cf.cf_copy_stage(ctx, src, dst, stream)
+            if ev:
+                ev[1].record(stream)
+        kernel_bytes = {"copy": copy_bytes}
+        dominant = "copy"
+    else:
+        if args.config == 5:
+            lost = wl.lost
+            grad_stages = [cf.Stage(ctx, g) for g in wl.grads]
+            ip, inx = lost - 1, lost + 1
+        else:
+            lost = 1
+            grad_stages = [cf.Stage(ctx, wl.grads[0]), cf.Stage(ctx, wl.grads[2])]
+            ip, inx = 0, 1
+        prev, nxt, out = (cf.Stage(ctx, wl.weights[i]) for i in (lost - 1, lost + 1, lost))
+        omega = torch.zeros(len(grad_stages), dtype=torch.float64, device=dev)
+        w_prev, w_next = omega[ip:ip + 1], omega[inx:inx + 1]
+        sq_bytes = sum(g.nbytes for g in grad_stages)
+        blend_bytes = 3 * out.nbytes
+        step_bytes = sq_bytes + blend_bytes
+        kernels = ["sqnorm", "blend"]
+
+        def step(ev=None):
+            if ev:
+                ev[0].record(stream)
+            cf.cf_stage_grad_sqnorm(ctx, grad_stages, omega, stream)
+            if ev:
+                ev[1].record(stream)
+            cf.cf_recover_stage_weighted_avg(ctx, prev, nxt, w_prev, w_next, out, stream)
+            if ev:
+                ev[2].record(stream)
+        kernel_bytes = {"sqnorm": sq_bytes, "blend": blend_bytes}
+        dominant = "blend"
+
+    for _ in range(args.warmup):
+        step()
+    torch.cuda.synchronize()
+
+    events = [[torch.cuda.Event(enable_timing=True) for _ in range(len(kernels) + 1)] for _ in range(args.steps)]
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for k in range(args.steps):
+        step(events[k])
+    torch.cuda.synchronize()
+    t1 = time.perf_counter()
+    ms_per_step = (t1 - t0) * 1e3 / args.steps
+    flags = ctx.read_flags()
+
+    kernel_ms = {}
+    for j, name in enumerate(kernels):
+        d = np.array([events[k][j].elapsed_time(events[k][j + 1]) for k in range(args.steps)])
+        kernel_ms[name] = {"avg": float(d.mean()), "median": float(np.median(d)), "min": float(d.min())}
+    gbps = step_bytes / (ms_per_step * 1e-3) / 1e9
+    dom_ms = kernel_ms[dominant]["avg"]
+    achieved = kernel_bytes[dominant] / (dom_ms * 1e-3) / 1e9
+
+    result = {
+        "metric": "stage_recovery_hbm_throughput",
+        "value": round(gbps, 1),
+        "unit": "GB/s",
+        "n_gpus": 1,
+        "steps": args.steps,
+        "warmup": args.warmup,
+        "ms_per_step": round(ms_per_step, 5),
+        "higher_is_better": True,
+        "scaling": "weak",
+        "vs_baseline": None,
+        "dtype": "f64",
+        "data": "synthetic",
+        "config": {
+            "workload": f"config {args.config}: {spec.name}",
+            "stage": {"d": spec.shape.d, "ffn": spec.shape.ffn, "layers": spec.shape.layers,
+                      "tensors": len(spec.shape.tensor_shapes()), "numel": numel},
+            "weight_dtype": spec.param_dtype, "grad_dtype": "f32",
+            "step": "+".join(kernels),
+            "algorithmic_bytes_per_step": int(step_bytes),
+            "frac_of_hbm_peak": round(gbps / HBM_PEAK_GBPS, 4),
+            "device_flags": flags,
+        },
+        "kernels": {name: {"ms_avg": round(v["avg"], 5), "ms_median": round(v["median"], 5),
+                           "ms_min": round(v["min"], 5),
+                           "GBps_avg": round(kernel_bytes[name] / (v["avg"] * 1e-3) / 1e9, 1)}
+                    for name, v in kernel_ms.items()},
+        "roofline": {
+            "kernel": {"blend": "cf_blend_kernel", "copy": "cf_copy_kernel"}[dominant],
+            "bound": "hbm",
+            "achieved": round(achieved, 1),
+            "peak": HBM_PEAK_GBPS,
+            "unit": "GB/s",
+            "frac": round(achieved / HBM_PEAK_GBPS, 4),
+            "traffic": None,
+        },
+    }
+
+    if not args.no_cpu_baseline:
+        result["cpu_baseline"] = cpu_baseline(args, wl, step_bytes, torch, workloads)
+    print(json.dumps(result), flush=True)
+    return 0
+
+
+def cpu_baseline(args, wl, step_bytes, torch, workloads):
+    """The oracle, as it stands, on this host's cores, over the same workload
+    (or a bounded part of it), repeated until about --cpu-seconds have passed."""
+    import oracle
+    threads = max(1, min(oracle.max_threads(), os.cpu_count() or 1))
+    if args.config == 4:
+        src = [workloads.to_numpy(t) for t in wl.weights[0] + wl.extra]
+        nbytes = 2 * sum(a.nbytes for a in src)
+        sample = "whole workload (39 tensors)"
+
+        def cpu_step():
+            oracle.copy_stage(src, threads)
+    else:
+        lost = wl.lost
+        if args.config == 5:
+            gidx = list(range(len(wl.grads)))
+        else:
+            gidx = [0, 2]
+        grads = [workloads.stage_to_numpy(wl.grads[i]) for i in gidx]
+        prev = workloads.stage_to_numpy(wl.weights[lost - 1])
+        nxt = workloads.stage_to_numpy(wl.weights[lost + 1])
+        nbytes = step_bytes
+        sample = "whole workload, same tensors as the GPU step"
+
+        def cpu_step():
+            om = [oracle.stage_grad_sqnorm(g, threads) for g in grads]
+            ip, inx = (lost - 1, lost + 1) if args.config == 5 else (0, 1)
+            oracle.recover_stage_weighted_avg(prev, nxt, om[ip], om[inx], threads)
+    t0 = time.perf_counter()
+    reps = 0
+    while True:
+        cpu_step()
+        reps += 1
+        el = time.perf_counter() - t0
+        if el * threads >= args.cpu_seconds or reps >= 50:
+            break
+    sec = el / reps
+    return {"value": round(nbytes / sec / 1e9, 2), "unit": "GB/s", "cores": threads, "kind": "oracle",
+            "ms_per_step": round(sec * 1e3, 2),
+            "sample": f"{sample}; {reps} repetition(s), {el:.1f} s wall on {threads} thread(s)"}
+
+
+if __name__ == "__main__":
+    sys.exit(main())

@@ -34,9 +34,10 @@
  *     nothing, copy nothing between host and device, and do not synchronise:
  *     they enqueue work on the caller's stream and return.
  *   - `stream` is a hipStream_t passed as void* (NULL = the default stream).
- *   - A context serialises its calls through device-side bookkeeping: calls that
- *     use the same cf_ctx must be ordered on one stream (or otherwise
- *     serialised by the caller).  Use one context per concurrent stream.
+ *   - Calls may be issued on any streams.  The only shared device state is the
+ *     context's flag word (updated atomically) and, per stage handle, the
+ *     scratch of cf_stage_grad_sqnorm: the same gradient-stage handle must not be
+ *     in two cf_stage_grad_sqnorm calls that may run at the same time.
  *   - Data-dependent conditions cannot be returned synchronously; they raise
  *     sticky bits in a device flag word read by cf_read_flags.
  */
@@ -93,10 +94,11 @@ typedef struct cf_tensor {
 
 /* Launch shape knobs.  Zero in any field keeps the default. */
 typedef struct cf_tuning {
-    uint32_t chunk_elems;          /* elements per work chunk; multiple of 2048, at most 2^20 */
-    uint32_t sqnorm_blocks_per_cu; /* resident 256-thread workgroups per compute unit */
-    uint32_t blend_blocks_per_cu;
-    uint32_t copy_blocks_per_cu;
+    uint32_t chunk_bytes;          /* bytes per work chunk: a power of two, 4 KiB .. 4 MiB (default 128 KiB) */
+    uint32_t sqnorm_blocks_per_cu; /* cap on the norm's first-pass grid, in workgroups per compute unit;
+                                      default 0 = one workgroup per chunk; at most 64 */
+    uint32_t reserved0;
+    uint32_t reserved1;
 } cf_tuning;
 
 typedef struct cf_ctx cf_ctx;      /* opaque: per-device bookkeeping */
@@ -106,7 +108,7 @@ typedef struct cf_stage cf_stage;  /* opaque: a stage's tensor list, uploaded on
  *      synchronise) ---- */
 
 /* Creates a context on HIP device `device`.  `tuning` may be NULL.  Allocates a
- * 256-byte device word block (ticket, flags).  Errors: CF_ERR_NULL, CF_ERR_HIP,
+ * 256-byte device word block (flags).  Errors: CF_ERR_NULL, CF_ERR_HIP,
  * CF_ERR_LIMIT (bad tuning value). */
 CF_API cf_status cf_ctx_create(int device, const cf_tuning *tuning, cf_ctx **out);
 
@@ -135,8 +137,8 @@ CF_API uint32_t cf_stage_num_chunks(const cf_stage *stage);
 /* ---- the hot path ---- */
 
 /* omega_s = sum over every tensor of grad_stages[s] of the sum of squares of its
- * elements, for s = 0 .. n_stages-1, in ONE kernel launch (groups of at most 64
- * stages per launch).  Paper: section "CheckFree: Memoryless Recovery",
+ * elements, for s = 0 .. n_stages-1, in ONE multi-tensor streaming launch over
+ * all stages (groups of at most 64 stages per launch) plus its second pass.  Paper: section "CheckFree: Memoryless Recovery",
  * omega_i = ||grad W^S_i||^2; Algorithm 1, the two "Receive" steps.
  *
  *   grad_stages  HOST array of n_stages stage handles (all tensors CF_F32)
@@ -144,11 +146,12 @@ CF_API uint32_t cf_stage_num_chunks(const cf_stage *stage);
  *
  * Elements are squared and accumulated in binary32 per lane, reduced per
  * wavefront to one binary32 partial per (chunk, wavefront) at a fixed slot, and
- * the partials of a stage are summed in binary64 in a fixed order by the last
- * workgroup to finish: the result is bit-identical from run to run and does not
- * depend on the launch shape.  An empty stage gives 0.  A non-finite result
+ * the partials of a stage are summed in binary64 in a fixed order by a second,
+ * tiny kernel enqueued right behind the first: the result is bit-identical from
+ * run to run and does not depend on the grid size.  An empty stage gives 0.  A non-finite result
  * raises CF_FLAG_NONFINITE_OMEGA.  The same stage handle must not appear in two
- * sqnorm calls that run concurrently.
+ * sqnorm calls that run concurrently (each handle owns its partial-sum scratch:
+ * 16 bytes per chunk, allocated by cf_stage_create).
  * Errors: CF_ERR_NULL, CF_ERR_DTYPE, CF_ERR_CONTEXT, CF_ERR_LIMIT, CF_ERR_HIP. */
 CF_API cf_status cf_stage_grad_sqnorm(cf_ctx *ctx, const cf_stage *const *grad_stages, uint32_t n_stages,
                                double *d_omega_out, void *stream);
@@ -198,15 +201,16 @@ CF_API cf_status cf_read_flags(cf_ctx *ctx, void *stream, uint32_t *flags, int c
 
 /* ---- host-only helpers (no device needed) ---- */
 
-/* Number of work chunks a tensor list is cut into with `chunk_elems` elements per
- * chunk (every tensor starts a new chunk; an empty tensor has none).  Returns
- * UINT64_MAX on a NULL list with num_tensors > 0 or chunk_elems == 0. */
-CF_API uint64_t cf_plan_num_chunks(const cf_tensor *tensors, uint32_t num_tensors, uint32_t chunk_elems);
+/* Number of work chunks a tensor list is cut into with `chunk_bytes` bytes per
+ * chunk (every tensor starts a new chunk; an empty tensor has none).  Only numel
+ * and dtype of the descriptors are read.  Returns UINT64_MAX on a NULL list with
+ * num_tensors > 0, an unknown dtype or an invalid chunk_bytes. */
+CF_API uint64_t cf_plan_num_chunks(const cf_tensor *tensors, uint32_t num_tensors, uint32_t chunk_bytes);
 
 /* Writes the chunk plan into HOST arrays of capacity `cap` chunks: the tensor
  * each chunk belongs to, its first element and its length in elements.  Returns
  * CF_ERR_LIMIT if cap is too small. */
-CF_API cf_status cf_plan_chunks(const cf_tensor *tensors, uint32_t num_tensors, uint32_t chunk_elems,
+CF_API cf_status cf_plan_chunks(const cf_tensor *tensors, uint32_t num_tensors, uint32_t chunk_bytes,
                          uint32_t *chunk_tensor, uint64_t *chunk_first, uint32_t *chunk_len, uint64_t cap);
 
 /* The tuning values in effect when `tuning` is NULL or holds zeros. */

@@ -44,8 +44,8 @@ class CfTensor(ctypes.Structure):
 
 
 class CfTuning(ctypes.Structure):
-    _fields_ = [("chunk_elems", ctypes.c_uint32), ("sqnorm_blocks_per_cu", ctypes.c_uint32),
-                ("blend_blocks_per_cu", ctypes.c_uint32), ("copy_blocks_per_cu", ctypes.c_uint32)]
+    _fields_ = [("chunk_bytes", ctypes.c_uint32), ("sqnorm_blocks_per_cu", ctypes.c_uint32),
+                ("reserved0", ctypes.c_uint32), ("reserved1", ctypes.c_uint32)]
 
 
 class CheckFreeError(RuntimeError):
@@ -157,7 +157,7 @@ def tensor_descriptors(tensors):
 
 
 class Context:
-    """cf_ctx: per-device bookkeeping (ticket and flag words).  One per stream."""
+    """cf_ctx: per-device bookkeeping (launch shape, sticky flag word)."""
 
     def __init__(self, device=0, **tuning):
         import torch
@@ -266,7 +266,7 @@ def cf_copy_stage(ctx: Context, src: Stage, dst: Stage, stream=None):
     return dst
 
 
-def plan_chunks(numels, chunk_elems, dtype=CF_F32):
+def plan_chunks(numels, chunk_bytes, dtype=CF_F32):
     """Host-only: the chunk plan (tensor index, first element, length) the
     library would use for tensors of the given element counts."""
     n = len(numels)
@@ -276,12 +276,12 @@ def plan_chunks(numels, chunk_elems, dtype=CF_F32):
         arr[i].numel = int(m)
         arr[i].dtype = dtype
     lib = load_library()
-    total = lib.cf_plan_num_chunks(arr, n, int(chunk_elems))
+    total = lib.cf_plan_num_chunks(arr, n, int(chunk_bytes))
     if total == 2 ** 64 - 1:
         raise CheckFreeError(CF_ERR_LIMIT, "cf_plan_num_chunks")
     cap = max(int(total), 1)
     ct = (ctypes.c_uint32 * cap)()
     cf = (ctypes.c_uint64 * cap)()
     cl = (ctypes.c_uint32 * cap)()
-    _check(lib.cf_plan_chunks(arr, n, int(chunk_elems), ct, cf, cl, int(total)), "cf_plan_chunks")
+    _check(lib.cf_plan_chunks(arr, n, int(chunk_bytes), ct, cf, cl, int(total)), "cf_plan_chunks")
     return [(ct[i], cf[i], cl[i]) for i in range(int(total))]

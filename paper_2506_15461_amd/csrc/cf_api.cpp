@@ -14,13 +14,12 @@
 
 namespace {
 
-constexpr uint32_t kDefaultChunkElems = 32768;   // 128 KiB of fp32 per chunk
-constexpr uint32_t kDefaultSqnormBlocksPerCu = 8;
-constexpr uint32_t kDefaultBlendBlocksPerCu = 8;
-constexpr uint32_t kDefaultCopyBlocksPerCu = 8;
-constexpr uint32_t kMaxChunkElems = 1u << 20;
-constexpr uint32_t kChunkElemsGranule = 2048;    // keeps chunk boundaries 16-byte aligned relative to the tensor start
+constexpr uint32_t kDefaultChunkBytes = 128u << 10;   // 32 tiles of 4 KiB
+constexpr uint32_t kMinChunkBytes = CF_TILE_BYTES;
+constexpr uint32_t kMaxChunkBytes = 4u << 20;
+constexpr uint32_t kDefaultSqnormBlocksPerCu = 0;     // 0: one workgroup per chunk
 constexpr uint64_t kMaxChunksPerStage = 1ull << 31;
+constexpr uint64_t kMaxGrid = (1ull << 31) - 1;
 constexpr size_t kCtxWordBytes = 256;
 
 std::atomic<uint64_t> g_next_stage_id{1};
@@ -39,6 +38,7 @@ struct cf_ctx {
     int device = 0;
     int num_cu = 0;
     cf_tuning tuning{};
+    uint32_t tile_shift = 0;   // log2(chunk_bytes / CF_TILE_BYTES)
     uint32_t *d_words = nullptr;
     // Pairs (input stage id, output stage id) whose congruence and aliasing have been checked.
     std::vector<std::pair<uint64_t, uint64_t>> checked;
@@ -88,7 +88,12 @@ cf_status check_tensor(const cf_tensor &t)
     return CF_OK;
 }
 
-uint64_t chunks_of(uint64_t numel, uint32_t chunk_elems) { return (numel + chunk_elems - 1) / chunk_elems; }
+uint64_t chunks_of(uint64_t numel, uint64_t chunk_elems) { return (numel + chunk_elems - 1) / chunk_elems; }
+
+bool valid_chunk_bytes(uint32_t b)
+{
+    return b >= kMinChunkBytes && b <= kMaxChunkBytes && (b & (b - 1)) == 0;
+}
 
 struct Range {
     uint64_t lo, hi;
@@ -176,10 +181,11 @@ void forget_stage(cf_ctx *ctx, uint64_t id)
             v.end());
 }
 
-uint32_t grid_for(const cf_ctx *ctx, uint32_t n_chunks, uint32_t blocks_per_cu)
+uint32_t sqnorm_grid(const cf_ctx *ctx, uint32_t n_chunks)
 {
-    uint64_t cap = (uint64_t)ctx->num_cu * blocks_per_cu;
-    uint64_t g = std::min<uint64_t>(n_chunks, cap);
+    uint64_t g = n_chunks;
+    if (ctx->tuning.sqnorm_blocks_per_cu)
+        g = std::min<uint64_t>(g, (uint64_t)ctx->num_cu * ctx->tuning.sqnorm_blocks_per_cu);
     return (uint32_t)std::max<uint64_t>(g, 1);
 }
 
@@ -190,10 +196,10 @@ extern "C" {
 void cf_default_tuning(cf_tuning *out)
 {
     if (!out) return;
-    out->chunk_elems = kDefaultChunkElems;
+    out->chunk_bytes = kDefaultChunkBytes;
     out->sqnorm_blocks_per_cu = kDefaultSqnormBlocksPerCu;
-    out->blend_blocks_per_cu = kDefaultBlendBlocksPerCu;
-    out->copy_blocks_per_cu = kDefaultCopyBlocksPerCu;
+    out->reserved0 = 0;
+    out->reserved1 = 0;
 }
 
 const char *cf_status_string(cf_status status)
@@ -212,21 +218,26 @@ const char *cf_status_string(cf_status status)
     }
 }
 
-uint64_t cf_plan_num_chunks(const cf_tensor *tensors, uint32_t num_tensors, uint32_t chunk_elems)
+uint64_t cf_plan_num_chunks(const cf_tensor *tensors, uint32_t num_tensors, uint32_t chunk_bytes)
 {
-    if ((num_tensors && !tensors) || chunk_elems == 0) return UINT64_MAX;
+    if ((num_tensors && !tensors) || !valid_chunk_bytes(chunk_bytes)) return UINT64_MAX;
     uint64_t n = 0;
-    for (uint32_t t = 0; t < num_tensors; ++t) n += chunks_of(tensors[t].numel, chunk_elems);
+    for (uint32_t t = 0; t < num_tensors; ++t) {
+        if (tensors[t].dtype != CF_F32 && tensors[t].dtype != CF_BF16) return UINT64_MAX;
+        n += chunks_of(tensors[t].numel, chunk_bytes / elem_size(tensors[t].dtype));
+    }
     return n;
 }
 
-cf_status cf_plan_chunks(const cf_tensor *tensors, uint32_t num_tensors, uint32_t chunk_elems,
+cf_status cf_plan_chunks(const cf_tensor *tensors, uint32_t num_tensors, uint32_t chunk_bytes,
                          uint32_t *chunk_tensor, uint64_t *chunk_first, uint32_t *chunk_len, uint64_t cap)
 {
     if ((num_tensors && !tensors) || !chunk_tensor || !chunk_first || !chunk_len) return CF_ERR_NULL;
-    if (chunk_elems == 0) return CF_ERR_LIMIT;
+    if (!valid_chunk_bytes(chunk_bytes)) return CF_ERR_LIMIT;
     uint64_t c = 0;
     for (uint32_t t = 0; t < num_tensors; ++t) {
+        if (tensors[t].dtype != CF_F32 && tensors[t].dtype != CF_BF16) return CF_ERR_DTYPE;
+        const uint64_t chunk_elems = chunk_bytes / elem_size(tensors[t].dtype);
         for (uint64_t first = 0; first < tensors[t].numel; first += chunk_elems) {
             if (c >= cap) return CF_ERR_LIMIT;
             chunk_tensor[c] = t;
@@ -245,13 +256,10 @@ cf_status cf_ctx_create(int device, const cf_tuning *tuning, cf_ctx **out)
     cf_tuning t;
     cf_default_tuning(&t);
     if (tuning) {
-        if (tuning->chunk_elems) t.chunk_elems = tuning->chunk_elems;
+        if (tuning->chunk_bytes) t.chunk_bytes = tuning->chunk_bytes;
         if (tuning->sqnorm_blocks_per_cu) t.sqnorm_blocks_per_cu = tuning->sqnorm_blocks_per_cu;
-        if (tuning->blend_blocks_per_cu) t.blend_blocks_per_cu = tuning->blend_blocks_per_cu;
-        if (tuning->copy_blocks_per_cu) t.copy_blocks_per_cu = tuning->copy_blocks_per_cu;
     }
-    if (t.chunk_elems % kChunkElemsGranule != 0 || t.chunk_elems > kMaxChunkElems) return CF_ERR_LIMIT;
-    if (t.sqnorm_blocks_per_cu > 64 || t.blend_blocks_per_cu > 64 || t.copy_blocks_per_cu > 64) return CF_ERR_LIMIT;
+    if (!valid_chunk_bytes(t.chunk_bytes) || t.sqnorm_blocks_per_cu > 64) return CF_ERR_LIMIT;
 
     int count = 0;
     if (hipGetDeviceCount(&count) != hipSuccess || device < 0 || device >= count) return CF_ERR_HIP;
@@ -265,6 +273,7 @@ cf_status cf_ctx_create(int device, const cf_tuning *tuning, cf_ctx **out)
     ctx->device = device;
     ctx->num_cu = num_cu;
     ctx->tuning = t;
+    for (uint32_t b = t.chunk_bytes / CF_TILE_BYTES; b > 1; b >>= 1) ++ctx->tile_shift;
     void *p = nullptr;
     if (hipMalloc(&p, kCtxWordBytes) != hipSuccess) {
         delete ctx;
@@ -296,14 +305,14 @@ cf_status cf_stage_create(cf_ctx *ctx, const cf_tensor *tensors, uint32_t num_te
 {
     if (!ctx || !out || (num_tensors && !tensors)) return CF_ERR_NULL;
     *out = nullptr;
-    const uint32_t chunk_elems = ctx->tuning.chunk_elems;
+    const uint32_t chunk_bytes = ctx->tuning.chunk_bytes;
     uint64_t n_chunks = 0;
     for (uint32_t t = 0; t < num_tensors; ++t) {
         cf_status st = check_tensor(tensors[t]);
         if (st != CF_OK) return st;
-        n_chunks += chunks_of(tensors[t].numel, chunk_elems);
+        n_chunks += chunks_of(tensors[t].numel, chunk_bytes / elem_size(tensors[t].dtype));
     }
-    if (n_chunks >= kMaxChunksPerStage) return CF_ERR_LIMIT;
+    if (n_chunks >= kMaxChunksPerStage || (n_chunks << ctx->tile_shift) > kMaxGrid) return CF_ERR_LIMIT;
 
     cf_stage *stage = new (std::nothrow) cf_stage;
     if (!stage) return CF_ERR_LIMIT;
@@ -325,6 +334,7 @@ cf_status cf_stage_create(cf_ctx *ctx, const cf_tensor *tensors, uint32_t num_te
         stage->numel += d.numel;
         stage->nbytes += d.numel * elem_size(d.dtype);
         if (d.dtype != CF_F32) stage->all_f32 = false;
+        const uint64_t chunk_elems = chunk_bytes / elem_size(d.dtype);
         for (uint64_t first = 0; first < d.numel; first += chunk_elems) {
             CfChunk c;
             c.addr = h.addr + first * elem_size(d.dtype);
@@ -403,7 +413,7 @@ cf_status cf_stage_grad_sqnorm(cf_ctx *ctx, const cf_stage *const *grad_stages, 
         args.total_chunks = (uint32_t)total;
         args.omega_out = d_omega_out + base;
         args.words = ctx->d_words;
-        const uint32_t grid = grid_for(ctx, args.total_chunks, ctx->tuning.sqnorm_blocks_per_cu);
+        const uint32_t grid = sqnorm_grid(ctx, args.total_chunks);
         if (cf_launch_sqnorm(args, grid, static_cast<hipStream_t>(stream)) != hipSuccess) return CF_ERR_HIP;
     }
     return CF_OK;
@@ -422,9 +432,8 @@ cf_status cf_recover_stage_weighted_avg(cf_ctx *ctx, const cf_stage *prev, const
     if (lost->n_chunks == 0) return CF_OK;
     DeviceGuard guard(ctx->device);
     if (!guard.ok()) return CF_ERR_HIP;
-    const uint32_t grid = grid_for(ctx, lost->n_chunks, ctx->tuning.blend_blocks_per_cu);
-    if (cf_launch_blend(prev->d_chunks, next->d_chunks, lost->d_chunks, lost->n_chunks, d_omega_prev,
-                        d_omega_next, ctx->d_words, grid, static_cast<hipStream_t>(stream)) != hipSuccess)
+    if (cf_launch_blend(prev->d_chunks, next->d_chunks, lost->d_chunks, lost->n_chunks, ctx->tile_shift,
+                        d_omega_prev, d_omega_next, ctx->d_words, static_cast<hipStream_t>(stream)) != hipSuccess)
         return CF_ERR_HIP;
     return CF_OK;
 }
@@ -438,9 +447,8 @@ cf_status cf_copy_stage(cf_ctx *ctx, const cf_stage *src, cf_stage *dst, void *s
     if (dst->n_chunks == 0) return CF_OK;
     DeviceGuard guard(ctx->device);
     if (!guard.ok()) return CF_ERR_HIP;
-    const uint32_t grid = grid_for(ctx, dst->n_chunks, ctx->tuning.copy_blocks_per_cu);
-    if (cf_launch_copy(src->d_chunks, dst->d_chunks, dst->n_chunks, grid, static_cast<hipStream_t>(stream)) !=
-        hipSuccess)
+    if (cf_launch_copy(src->d_chunks, dst->d_chunks, dst->n_chunks, ctx->tile_shift,
+                       static_cast<hipStream_t>(stream)) != hipSuccess)
         return CF_ERR_HIP;
     return CF_OK;
 }

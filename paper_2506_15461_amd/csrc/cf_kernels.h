@@ -17,12 +17,13 @@ struct CfChunk {
     uint32_t dtype;  // CF_F32 / CF_BF16
 };
 
-constexpr int CF_THREADS = 256;          // workgroup size of every kernel: 4 wavefronts
+constexpr int CF_THREADS = 256;          // workgroup size of the streaming kernels: 4 wavefronts
 constexpr int CF_WAVES = CF_THREADS / 64;
+constexpr int CF_FINALIZE_THREADS = 1024;   // workgroup size of the norm's second pass
 constexpr int CF_MAX_SEG = 64;           // stages per sqnorm launch
+constexpr uint32_t CF_TILE_BYTES = CF_THREADS * 16u;   // one 16-byte vector per lane: the blend/copy work unit
 
 // Device word block owned by a context.
-constexpr int CF_WORD_TICKET = 0;        // workgroups finished in the running sqnorm launch
 constexpr int CF_WORD_FLAGS = 1;         // sticky CF_FLAG_* bits
 
 struct CfSqnormSeg {
@@ -40,13 +41,15 @@ struct CfSqnormArgs {
     uint32_t *words;         // context word block
 };
 
+// First pass over `grid` workgroups, then the fixed-order second pass (one workgroup per stage).
 hipError_t cf_launch_sqnorm(const CfSqnormArgs &args, uint32_t grid, hipStream_t stream);
 
+// One workgroup per tile; a chunk holds at most 2^tile_shift tiles of CF_TILE_BYTES.
 hipError_t cf_launch_blend(const CfChunk *prev, const CfChunk *next, const CfChunk *lost, uint32_t n_chunks,
-                           const double *d_omega_prev, const double *d_omega_next, uint32_t *words,
-                           uint32_t grid, hipStream_t stream);
+                           uint32_t tile_shift, const double *d_omega_prev, const double *d_omega_next,
+                           uint32_t *words, hipStream_t stream);
 
-hipError_t cf_launch_copy(const CfChunk *src, const CfChunk *dst, uint32_t n_chunks, uint32_t grid,
+hipError_t cf_launch_copy(const CfChunk *src, const CfChunk *dst, uint32_t n_chunks, uint32_t tile_shift,
                           hipStream_t stream);
 
 #endif

@@ -2,9 +2,10 @@
 //
 // All three are HBM-streaming kernels: a grid of 256-thread workgroups walks a
 // device-side chunk table (one multi-tensor launch per operation), every lane
-// moves 16 bytes per memory instruction, and there is no reuse, so nothing is
-// staged through LDS on the streaming side.  Nothing here is a contraction, so
-// no MFMA.
+// moves 16 bytes per memory instruction with the streaming (non-temporal) cache
+// policy, and there is no reuse, so nothing is staged through LDS on the
+// streaming side (LDS carries only the fixed-order second pass of the norm).
+// Nothing here is a contraction, so no MFMA.
 //
 // Paper: "CheckFree: Memoryless Recovery" (omega = squared gradient norm of a
 // stage; the weighted-average display equation; Algorithm 1) and "CheckFree+:
@@ -124,16 +125,14 @@ __device__ __forceinline__ float chunk_sqsum_f32(gcf32 p, uint32_t len, uint32_t
     return (a0 + a1) + (a2 + a3);
 }
 
-// Workgroup b takes chunks b, b + grid, b + 2 grid, ...  Each wavefront writes
-// the sum of squares of its lanes' share of a chunk to slot (chunk, wavefront)
-// of the owning stage's partial array, so the partials do not depend on the
-// grid size.  The last workgroup to finish (ticket) adds each stage's partials
-// in binary64 in a fixed order and writes omega.
-__global__ __launch_bounds__(CF_THREADS) void cf_sqnorm_kernel(CfSqnormArgs args)
+// First pass.  Workgroup b takes chunks b, b + grid, b + 2 grid, ...  Each
+// wavefront writes the sum of squares of its lanes' share of a chunk to slot
+// (chunk, wavefront) of the owning stage's partial array, so the partials do not
+// depend on the grid size.  There is no fence and no atomic on this streaming
+// pass: on this chip an agent-scope release per workgroup (an L2 write-back)
+// cuts a read-only stream to under 40 % of what it reaches without.
+__global__ __launch_bounds__(CF_THREADS) void cf_sqnorm_partials_kernel(CfSqnormArgs args)
 {
-    __shared__ double red[CF_THREADS];
-    __shared__ uint32_t s_is_last;
-
     const uint32_t tid = threadIdx.x;
     const uint32_t wave = tid >> 6;
     const uint32_t lane = tid & 63u;
@@ -147,37 +146,31 @@ __global__ __launch_bounds__(CF_THREADS) void cf_sqnorm_kernel(CfSqnormArgs args
         float w = wave_sum(t);
         if (lane == 0) args.seg[s].partials[(uint64_t)local * CF_WAVES + wave] = w;
     }
+}
 
-    // Publish this workgroup's partials, then take a ticket.
-    __threadfence();
+// Second pass, stream-ordered after the first: workgroup k adds the partials of
+// stage k in binary64 in a fixed order (lane-strided serial sums, then a fixed
+// LDS tree) and writes omega_k.
+__global__ __launch_bounds__(CF_FINALIZE_THREADS) void cf_sqnorm_finalize_kernel(CfSqnormArgs args)
+{
+    __shared__ double red[CF_FINALIZE_THREADS];
+    const uint32_t tid = threadIdx.x;
+    const uint32_t k = blockIdx.x;
+    const float *part = args.seg[k].partials;
+    const uint64_t np = (uint64_t)args.seg[k].n_chunks * CF_WAVES;
+    double acc = 0.0;
+    for (uint64_t i = tid; i < np; i += CF_FINALIZE_THREADS) acc += (double)part[i];
+    red[tid] = acc;
     __syncthreads();
+    for (uint32_t off = CF_FINALIZE_THREADS / 2; off > 0; off >>= 1) {
+        if (tid < off) red[tid] += red[tid + off];
+        __syncthreads();
+    }
     if (tid == 0) {
-        uint32_t ticket = atomicAdd(&args.words[CF_WORD_TICKET], 1u);
-        s_is_last = (ticket == gridDim.x - 1u) ? 1u : 0u;
+        const double omega = red[0];
+        args.omega_out[k] = omega;
+        if (!(omega - omega == 0.0)) atomicOr(&args.words[CF_WORD_FLAGS], kFlagNonfiniteOmega);
     }
-    __syncthreads();
-    if (!s_is_last) return;
-    __threadfence();   // see every other workgroup's partials
-
-    for (uint32_t k = 0; k < args.n_seg; ++k) {
-        const float *part = args.seg[k].partials;
-        const uint64_t np = (uint64_t)args.seg[k].n_chunks * CF_WAVES;
-        double acc = 0.0;
-        for (uint64_t i = tid; i < np; i += CF_THREADS) acc += (double)part[i];
-        red[tid] = acc;
-        __syncthreads();
-        for (uint32_t off = CF_THREADS / 2; off > 0; off >>= 1) {
-            if (tid < off) red[tid] += red[tid + off];
-            __syncthreads();
-        }
-        if (tid == 0) {
-            double omega = red[0];
-            args.omega_out[k] = omega;
-            if (!(omega - omega == 0.0)) atomicOr(&args.words[CF_WORD_FLAGS], kFlagNonfiniteOmega);
-        }
-        __syncthreads();
-    }
-    if (tid == 0) args.words[CF_WORD_TICKET] = 0u;   // ready for the next launch on this context
 }
 
 // ---------------------------------------------------------------------------
@@ -233,118 +226,105 @@ __device__ __forceinline__ uint32_t blend_bf16_pair(const BlendWeights &w, uint3
     return lo | (hi << 16);
 }
 
-template <int kUnroll>
-__device__ __forceinline__ void blend_chunk_f32(const BlendWeights &w, gcf32 pa, gcf32 pb, gf32 po, uint32_t len,
-                                                uint32_t tid)
+// One workgroup blends one *tile*: 256 sixteen-byte vectors of each of the three
+// streams, one vector per lane.  Workgroups are dispatched in tile order, so at
+// any moment the chip reads two narrow moving windows and writes a third; on
+// this memory system that ordering sustains about a fifth more bandwidth for a
+// two-read-one-write stream than a resident grid striding over large chunks.
+// Tile 0 of a chunk also takes the few elements before and after the 16-byte
+// aligned body.
+__device__ __forceinline__ void blend_tile_f32(const BlendWeights &w, gcf32 pa, gcf32 pb, gf32 po, uint32_t len,
+                                               uint32_t tile, uint32_t tid)
 {
     const uint32_t mis = (uint32_t)((uint64_t)pa & 15u);
     if (mis != (uint32_t)((uint64_t)pb & 15u) || mis != (uint32_t)((uint64_t)po & 15u)) {
         // The three tensors sit differently inside their 16-byte lines: dword path.
-        for (uint32_t i = tid; i < len; i += CF_THREADS) po[i] = blend_to_f32(w, pa[i], pb[i]);
+#pragma unroll
+        for (uint32_t j = 0; j < 4; ++j) {
+            const uint32_t i = tile * (4u * CF_THREADS) + j * CF_THREADS + tid;
+            if (i < len) po[i] = blend_to_f32(w, pa[i], pb[i]);
+        }
         return;
     }
     const uint32_t head = head_elems((uint64_t)pa, 4u, len);
-    if (tid < head) po[tid] = blend_to_f32(w, pa[tid], pb[tid]);
-    gcf32x4 qa = (gcf32x4)(pa + head);
-    gcf32x4 qb = (gcf32x4)(pb + head);
-    gf32x4 qo = (gf32x4)(po + head);
     const uint32_t rem = len - head;
     const uint32_t n4 = rem >> 2;
-    uint32_t i = tid;
-    for (; i + (kUnroll - 1) * CF_THREADS < n4; i += kUnroll * CF_THREADS) {
-        f32x4 a[kUnroll], b[kUnroll];
-#pragma unroll
-        for (int u = 0; u < kUnroll; ++u) {
-            a[u] = __builtin_nontemporal_load(qa + i + u * CF_THREADS);
-            b[u] = __builtin_nontemporal_load(qb + i + u * CF_THREADS);
-        }
-#pragma unroll
-        for (int u = 0; u < kUnroll; ++u) {
-            f32x4 o;
-            o.x = blend_to_f32(w, a[u].x, b[u].x);
-            o.y = blend_to_f32(w, a[u].y, b[u].y);
-            o.z = blend_to_f32(w, a[u].z, b[u].z);
-            o.w = blend_to_f32(w, a[u].w, b[u].w);
-            __builtin_nontemporal_store(o, qo + i + u * CF_THREADS);
-        }
-    }
-    for (; i < n4; i += CF_THREADS) {
-        f32x4 a = __builtin_nontemporal_load(qa + i);
-        f32x4 b = __builtin_nontemporal_load(qb + i);
+    const uint32_t v = tile * CF_THREADS + tid;
+    if (v < n4) {
+        const f32x4 a = __builtin_nontemporal_load((gcf32x4)(pa + head) + v);
+        const f32x4 b = __builtin_nontemporal_load((gcf32x4)(pb + head) + v);
         f32x4 o;
         o.x = blend_to_f32(w, a.x, b.x);
         o.y = blend_to_f32(w, a.y, b.y);
         o.z = blend_to_f32(w, a.z, b.z);
         o.w = blend_to_f32(w, a.w, b.w);
-        __builtin_nontemporal_store(o, qo + i);
+        __builtin_nontemporal_store(o, (gf32x4)(po + head) + v);
     }
-    const uint32_t tail = rem & 3u;
-    const uint32_t tbase = head + (n4 << 2);
-    if (tid < tail) po[tbase + tid] = blend_to_f32(w, pa[tbase + tid], pb[tbase + tid]);
+    if (tile == 0) {
+        if (tid < head) po[tid] = blend_to_f32(w, pa[tid], pb[tid]);
+        const uint32_t tail = rem & 3u;
+        const uint32_t tbase = head + (n4 << 2);
+        if (tid < tail) po[tbase + tid] = blend_to_f32(w, pa[tbase + tid], pb[tbase + tid]);
+    }
 }
 
-template <int kUnroll>
-__device__ __forceinline__ void blend_chunk_bf16(const BlendWeights &w, gcu16 pa, gcu16 pb, gu16 po, uint32_t len,
-                                                 uint32_t tid)
+__device__ __forceinline__ uint16_t blend_to_bf16(const BlendWeights &w, uint16_t a, uint16_t b)
+{
+    return (uint16_t)f64_to_bf16_bits(blend_f64(w, bf16_bits_to_f64(a), bf16_bits_to_f64(b)));
+}
+
+__device__ __forceinline__ void blend_tile_bf16(const BlendWeights &w, gcu16 pa, gcu16 pb, gu16 po, uint32_t len,
+                                                uint32_t tile, uint32_t tid)
 {
     const uint32_t mis = (uint32_t)((uint64_t)pa & 15u);
     if (mis != (uint32_t)((uint64_t)pb & 15u) || mis != (uint32_t)((uint64_t)po & 15u)) {
-        for (uint32_t i = tid; i < len; i += CF_THREADS)
-            po[i] = (uint16_t)f64_to_bf16_bits(blend_f64(w, bf16_bits_to_f64(pa[i]), bf16_bits_to_f64(pb[i])));
+#pragma unroll
+        for (uint32_t j = 0; j < 8; ++j) {
+            const uint32_t i = tile * (8u * CF_THREADS) + j * CF_THREADS + tid;
+            if (i < len) po[i] = blend_to_bf16(w, pa[i], pb[i]);
+        }
         return;
     }
     const uint32_t head = head_elems((uint64_t)pa, 2u, len);
-    if (tid < head)
-        po[tid] = (uint16_t)f64_to_bf16_bits(blend_f64(w, bf16_bits_to_f64(pa[tid]), bf16_bits_to_f64(pb[tid])));
-    gcu32x4 qa = (gcu32x4)(pa + head);
-    gcu32x4 qb = (gcu32x4)(pb + head);
-    gu32x4 qo = (gu32x4)(po + head);
     const uint32_t rem = len - head;
     const uint32_t n8 = rem >> 3;
-    uint32_t i = tid;
-    for (; i + (kUnroll - 1) * CF_THREADS < n8; i += kUnroll * CF_THREADS) {
-        u32x4 a[kUnroll], b[kUnroll];
-#pragma unroll
-        for (int u = 0; u < kUnroll; ++u) {
-            a[u] = __builtin_nontemporal_load(qa + i + u * CF_THREADS);
-            b[u] = __builtin_nontemporal_load(qb + i + u * CF_THREADS);
-        }
-#pragma unroll
-        for (int u = 0; u < kUnroll; ++u) {
-            u32x4 o;
-            o.x = blend_bf16_pair(w, a[u].x, b[u].x);
-            o.y = blend_bf16_pair(w, a[u].y, b[u].y);
-            o.z = blend_bf16_pair(w, a[u].z, b[u].z);
-            o.w = blend_bf16_pair(w, a[u].w, b[u].w);
-            __builtin_nontemporal_store(o, qo + i + u * CF_THREADS);
-        }
-    }
-    for (; i < n8; i += CF_THREADS) {
-        u32x4 a = __builtin_nontemporal_load(qa + i);
-        u32x4 b = __builtin_nontemporal_load(qb + i);
+    const uint32_t v = tile * CF_THREADS + tid;
+    if (v < n8) {
+        const u32x4 a = __builtin_nontemporal_load((gcu32x4)(pa + head) + v);
+        const u32x4 b = __builtin_nontemporal_load((gcu32x4)(pb + head) + v);
         u32x4 o;
         o.x = blend_bf16_pair(w, a.x, b.x);
         o.y = blend_bf16_pair(w, a.y, b.y);
         o.z = blend_bf16_pair(w, a.z, b.z);
         o.w = blend_bf16_pair(w, a.w, b.w);
-        __builtin_nontemporal_store(o, qo + i);
+        __builtin_nontemporal_store(o, (gu32x4)(po + head) + v);
     }
-    const uint32_t tail = rem & 7u;
-    const uint32_t tbase = head + (n8 << 3);
-    if (tid < tail) {
-        const uint32_t k = tbase + tid;
-        po[k] = (uint16_t)f64_to_bf16_bits(blend_f64(w, bf16_bits_to_f64(pa[k]), bf16_bits_to_f64(pb[k])));
+    if (tile == 0) {
+        if (tid < head) po[tid] = blend_to_bf16(w, pa[tid], pb[tid]);
+        const uint32_t tail = rem & 7u;
+        const uint32_t tbase = head + (n8 << 3);
+        if (tid < tail) po[tbase + tid] = blend_to_bf16(w, pa[tbase + tid], pb[tbase + tid]);
     }
 }
 
-// The norm-to-weight scaling is the kernel's prologue: every workgroup reads the
-// two binary64 omegas from device memory and derives identical weights.
+// Workgroup index -> (chunk, tile of the chunk).  A chunk holds at most
+// 2^tile_shift tiles; a workgroup whose tile lies past the chunk's end retires
+// at once.  The norm-to-weight scaling is the kernel's prologue: every
+// workgroup reads the two binary64 omegas from device memory and derives
+// identical weights (the division overlaps the tile's loads).
 __global__ __launch_bounds__(CF_THREADS) void cf_blend_kernel(const CfChunk *prev, const CfChunk *next,
-                                                              const CfChunk *lost, uint32_t n_chunks,
+                                                              const CfChunk *lost, uint32_t tile_shift,
                                                               const double *d_omega_prev,
                                                               const double *d_omega_next, uint32_t *words)
 {
     const uint32_t tid = threadIdx.x;
+    const uint32_t c = blockIdx.x >> tile_shift;
+    const uint32_t tile = blockIdx.x & ((1u << tile_shift) - 1u);
+    const CfChunk co = lost[c];
+    if (tile != 0 && (uint64_t)tile * CF_TILE_BYTES >= (uint64_t)co.len * (co.dtype == kDtypeF32 ? 4u : 2u)) return;
+    const CfChunk ca = prev[c];
+    const CfChunk cb = next[c];
+
     BlendWeights w;
     w.wp = *d_omega_prev;
     w.wn = *d_omega_next;
@@ -360,61 +340,57 @@ __global__ __launch_bounds__(CF_THREADS) void cf_blend_kernel(const CfChunk *pre
     }
     w.rcp = 1.0 / den;
 
-    for (uint32_t c = blockIdx.x; c < n_chunks; c += gridDim.x) {
-        const CfChunk ca = prev[c];
-        const CfChunk cb = next[c];
-        const CfChunk co = lost[c];
-        if (co.dtype == kDtypeF32)
-            blend_chunk_f32<4>(w, (gcf32)ca.addr, (gcf32)cb.addr, (gf32)co.addr, co.len, tid);
-        else
-            blend_chunk_bf16<4>(w, (gcu16)ca.addr, (gcu16)cb.addr, (gu16)co.addr, co.len, tid);
-    }
+    if (co.dtype == kDtypeF32)
+        blend_tile_f32(w, (gcf32)ca.addr, (gcf32)cb.addr, (gf32)co.addr, co.len, tile, tid);
+    else
+        blend_tile_bf16(w, (gcu16)ca.addr, (gcu16)cb.addr, (gu16)co.addr, co.len, tile, tid);
 }
 
 // ---------------------------------------------------------------------------
-// Bit-exact multi-tensor copy (CheckFree+).
+// Bit-exact multi-tensor copy (CheckFree+): same tile-per-workgroup walk.
 // ---------------------------------------------------------------------------
 
-template <int kUnroll>
 __global__ __launch_bounds__(CF_THREADS) void cf_copy_kernel(const CfChunk *src, const CfChunk *dst,
-                                                             uint32_t n_chunks)
+                                                             uint32_t tile_shift)
 {
     const uint32_t tid = threadIdx.x;
-    for (uint32_t c = blockIdx.x; c < n_chunks; c += gridDim.x) {
-        const CfChunk cs = src[c];
-        const CfChunk cd = dst[c];
-        const uint32_t esize = (cs.dtype == kDtypeF32) ? 4u : 2u;
-        const uint32_t nbytes = cs.len * esize;
-        gcu8 ps = (gcu8)cs.addr;
-        gu8 pd = (gu8)cd.addr;
-        if (((uint64_t)ps & 15u) != ((uint64_t)pd & 15u)) {
-            // Different position inside a 16-byte line: move whole elements.
-            if (esize == 4u) {
-                gcu32 s4 = (gcu32)ps;
-                gu32 d4 = (gu32)pd;
-                for (uint32_t i = tid; i < cs.len; i += CF_THREADS) d4[i] = s4[i];
-            } else {
-                gcu16 s2 = (gcu16)ps;
-                gu16 d2 = (gu16)pd;
-                for (uint32_t i = tid; i < cs.len; i += CF_THREADS) d2[i] = s2[i];
+    const uint32_t c = blockIdx.x >> tile_shift;
+    const uint32_t tile = blockIdx.x & ((1u << tile_shift) - 1u);
+    const CfChunk cd = dst[c];
+    const uint32_t esize = (cd.dtype == kDtypeF32) ? 4u : 2u;
+    const uint32_t nbytes = cd.len * esize;
+    if (tile != 0 && tile * CF_TILE_BYTES >= nbytes) return;
+    const CfChunk cs = src[c];
+    gcu8 ps = (gcu8)cs.addr;
+    gu8 pd = (gu8)cd.addr;
+    if (((uint64_t)ps & 15u) != ((uint64_t)pd & 15u)) {
+        // Different position inside a 16-byte line: move whole elements.
+        if (esize == 4u) {
+            gcu32 s4 = (gcu32)ps;
+            gu32 d4 = (gu32)pd;
+#pragma unroll
+            for (uint32_t j = 0; j < 4; ++j) {
+                const uint32_t i = tile * (4u * CF_THREADS) + j * CF_THREADS + tid;
+                if (i < cd.len) d4[i] = s4[i];
             }
-            continue;
+        } else {
+            gcu16 s2 = (gcu16)ps;
+            gu16 d2 = (gu16)pd;
+#pragma unroll
+            for (uint32_t j = 0; j < 8; ++j) {
+                const uint32_t i = tile * (8u * CF_THREADS) + j * CF_THREADS + tid;
+                if (i < cd.len) d2[i] = s2[i];
+            }
         }
-        const uint32_t head = head_elems((uint64_t)ps, 1u, nbytes);
+        return;
+    }
+    const uint32_t head = head_elems((uint64_t)ps, 1u, nbytes);
+    const uint32_t rem = nbytes - head;
+    const uint32_t n16 = rem >> 4;
+    const uint32_t v = tile * CF_THREADS + tid;
+    if (v < n16) __builtin_nontemporal_store(__builtin_nontemporal_load((gcu32x4)(ps + head) + v), (gu32x4)(pd + head) + v);
+    if (tile == 0) {
         if (tid < head) pd[tid] = ps[tid];
-        gcu32x4 qs = (gcu32x4)(ps + head);
-        gu32x4 qd = (gu32x4)(pd + head);
-        const uint32_t rem = nbytes - head;
-        const uint32_t n16 = rem >> 4;
-        uint32_t i = tid;
-        for (; i + (kUnroll - 1) * CF_THREADS < n16; i += kUnroll * CF_THREADS) {
-            u32x4 v[kUnroll];
-#pragma unroll
-            for (int u = 0; u < kUnroll; ++u) v[u] = __builtin_nontemporal_load(qs + i + u * CF_THREADS);
-#pragma unroll
-            for (int u = 0; u < kUnroll; ++u) __builtin_nontemporal_store(v[u], qd + i + u * CF_THREADS);
-        }
-        for (; i < n16; i += CF_THREADS) __builtin_nontemporal_store(__builtin_nontemporal_load(qs + i), qd + i);
         const uint32_t tail = rem & 15u;
         const uint32_t tbase = head + (n16 << 4);
         if (tid < tail) pd[tbase + tid] = ps[tbase + tid];
@@ -425,22 +401,28 @@ __global__ __launch_bounds__(CF_THREADS) void cf_copy_kernel(const CfChunk *src,
 
 hipError_t cf_launch_sqnorm(const CfSqnormArgs &args, uint32_t grid, hipStream_t stream)
 {
-    hipLaunchKernelGGL(cf_sqnorm_kernel, dim3(grid), dim3(CF_THREADS), 0, stream, args);
+    if (args.total_chunks != 0) {
+        hipLaunchKernelGGL(cf_sqnorm_partials_kernel, dim3(grid), dim3(CF_THREADS), 0, stream, args);
+        hipError_t e = hipGetLastError();
+        if (e != hipSuccess) return e;
+    }
+    hipLaunchKernelGGL(cf_sqnorm_finalize_kernel, dim3(args.n_seg), dim3(CF_FINALIZE_THREADS), 0, stream, args);
     return hipGetLastError();
 }
 
 hipError_t cf_launch_blend(const CfChunk *prev, const CfChunk *next, const CfChunk *lost, uint32_t n_chunks,
-                           const double *d_omega_prev, const double *d_omega_next, uint32_t *words,
-                           uint32_t grid, hipStream_t stream)
+                           uint32_t tile_shift, const double *d_omega_prev, const double *d_omega_next,
+                           uint32_t *words, hipStream_t stream)
 {
-    hipLaunchKernelGGL(cf_blend_kernel, dim3(grid), dim3(CF_THREADS), 0, stream, prev, next, lost, n_chunks,
-                       d_omega_prev, d_omega_next, words);
+    hipLaunchKernelGGL(cf_blend_kernel, dim3(n_chunks << tile_shift), dim3(CF_THREADS), 0, stream, prev, next, lost,
+                       tile_shift, d_omega_prev, d_omega_next, words);
     return hipGetLastError();
 }
 
-hipError_t cf_launch_copy(const CfChunk *src, const CfChunk *dst, uint32_t n_chunks, uint32_t grid,
+hipError_t cf_launch_copy(const CfChunk *src, const CfChunk *dst, uint32_t n_chunks, uint32_t tile_shift,
                           hipStream_t stream)
 {
-    hipLaunchKernelGGL(cf_copy_kernel<8>, dim3(grid), dim3(CF_THREADS), 0, stream, src, dst, n_chunks);
+    hipLaunchKernelGGL(cf_copy_kernel, dim3(n_chunks << tile_shift), dim3(CF_THREADS), 0, stream, src, dst,
+                       tile_shift);
     return hipGetLastError();
 }

@@ -48,14 +48,13 @@ def test_status_strings(lib):
 
 def test_default_tuning(lib):
     t = cf.default_tuning()
-    assert t["chunk_elems"] % 2048 == 0 and t["chunk_elems"] > 0
-    assert all(v > 0 for v in t.values())
+    assert t["chunk_bytes"] >= 4096 and t["chunk_bytes"] & (t["chunk_bytes"] - 1) == 0
 
 
 def test_chunk_plan_covers_every_element_once(lib):
     numels = [1, 0, 2047, 2048, 2049, 70000, 5, 32768 * 3]
     chunk = 4096
-    plan = cf.plan_chunks(numels, chunk)
+    plan = cf.plan_chunks(numels, chunk * 4)        # fp32: 16 KiB chunks hold 4096 elements
     seen = {t: [] for t in range(len(numels))}
     for t, first, length in plan:
         assert 0 < length <= chunk
@@ -77,26 +76,36 @@ def test_chunk_plan_model_shape(lib):
     shape = workloads.SPECS[3].shape
     numels = [int(np.prod(s)) for s in shape.tensor_shapes()]
     assert sum(numels) == 205_537_280 and len(numels) == 36
-    plan = cf.plan_chunks(numels, 32768)
+    plan = cf.plan_chunks(numels, 128 << 10)
     assert sum(l for _, _, l in plan) == sum(numels)
+    assert len(plan) == 6280
+    # bf16 chunks hold twice the elements in the same bytes
+    plan16 = cf.plan_chunks(numels, 128 << 10, cf.CF_BF16)
+    assert sum(l for _, _, l in plan16) == sum(numels) and max(l for _, _, l in plan16) == 65536
 
 
 def test_plan_argument_errors(lib):
     arr = (cf.CfTensor * 1)()
     arr[0].numel = 10
+    arr[0].numel = 3000
     assert lib.cf_plan_num_chunks(arr, 1, 0) == 2 ** 64 - 1
-    assert lib.cf_plan_num_chunks(None, 1, 16) == 2 ** 64 - 1
-    assert lib.cf_plan_num_chunks(None, 0, 16) == 0
+    assert lib.cf_plan_num_chunks(arr, 1, 5000) == 2 ** 64 - 1          # not a power of two
+    assert lib.cf_plan_num_chunks(arr, 1, 2048) == 2 ** 64 - 1          # below one tile
+    assert lib.cf_plan_num_chunks(None, 1, 4096) == 2 ** 64 - 1
+    assert lib.cf_plan_num_chunks(None, 0, 4096) == 0
+    assert lib.cf_plan_num_chunks(arr, 1, 4096) == 3
     ct = (ctypes.c_uint32 * 1)()
     cfirst = (ctypes.c_uint64 * 1)()
     cl = (ctypes.c_uint32 * 1)()
-    assert lib.cf_plan_chunks(arr, 1, 4, ct, cfirst, cl, 1) == cf.CF_ERR_LIMIT      # needs 3 slots
-    assert lib.cf_plan_chunks(arr, 1, 4, None, cfirst, cl, 8) == cf.CF_ERR_NULL
+    assert lib.cf_plan_chunks(arr, 1, 4096, ct, cfirst, cl, 1) == cf.CF_ERR_LIMIT      # needs 3 slots
+    assert lib.cf_plan_chunks(arr, 1, 4096, None, cfirst, cl, 8) == cf.CF_ERR_NULL
+    arr[0].dtype = 7
+    assert lib.cf_plan_num_chunks(arr, 1, 4096) == 2 ** 64 - 1
 
 
 def test_null_and_bad_arguments_without_a_device(lib):
     assert lib.cf_ctx_create(0, None, None) == cf.CF_ERR_NULL
-    bad = cf.CfTuning(chunk_elems=1000)
+    bad = cf.CfTuning(chunk_bytes=1000)
     h = ctypes.c_void_p()
     assert lib.cf_ctx_create(0, ctypes.byref(bad), ctypes.byref(h)) == cf.CF_ERR_LIMIT
     assert lib.cf_ctx_destroy(None) == cf.CF_OK

@@ -112,7 +112,7 @@ def test_sqnorm_closed_forms(ctx, dev):
 def test_sqnorm_is_bitwise_reproducible_and_launch_shape_independent(dev):
     wl = workloads.make_workload(1, device=dev, shape=workloads.StageShape(192, 512, 2))
     results = []
-    for tuning in ({}, {"sqnorm_blocks_per_cu": 1}, {"sqnorm_blocks_per_cu": 3}):
+    for tuning in ({}, {"sqnorm_blocks_per_cu": 1}, {"sqnorm_blocks_per_cu": 3}, {"sqnorm_blocks_per_cu": 8}):
         c = cf.Context(0, **tuning)
         handles = [cf.Stage(c, g) for g in wl.grads]
         for rep in range(3):
@@ -176,6 +176,30 @@ def test_blend_ragged_stage(ctx, dev, dtype):
         torch.cuda.synchronize()
         want = oracle.recover_stage_weighted_avg(np_stage(a), np_stage(b), wp, wn)
         assert_blend_close(np_stage(out), want)
+
+
+@pytest.mark.parametrize("chunk_bytes", [4096, 8192, 65536, 1 << 20])
+@pytest.mark.parametrize("dtype", ["f32", "bf16"])
+def test_blend_copy_and_sqnorm_for_other_chunk_sizes(dev, dtype, chunk_bytes):
+    """Chunk and tile boundaries move with the chunk size; results must not."""
+    c = cf.Context(0, chunk_bytes=chunk_bytes)
+    shapes = workloads.ragged_shapes(5) + [(3 * 65536 + 17,), (1024,), (2048,), (1025,), (262144,)]
+    a, b = _draw_pair(dev, shapes, dtype, 27)
+    out = [torch.full_like(t, float("nan")) for t in a]
+    w = _omega(dev, 3.7e-3, 1.9e-2)
+    cf.cf_recover_stage_weighted_avg(c, cf.Stage(c, a), cf.Stage(c, b), w[0:1], w[1:2], cf.Stage(c, out))
+    torch.cuda.synchronize()
+    assert_blend_close(np_stage(out), oracle.recover_stage_weighted_avg(np_stage(a), np_stage(b), 3.7e-3, 1.9e-2))
+    dst = [torch.zeros_like(t) for t in a]
+    cf.cf_copy_stage(c, cf.Stage(c, a), cf.Stage(c, dst))
+    torch.cuda.synchronize()
+    for g, wnt in zip(np_stage(dst), oracle.copy_stage(np_stage(a))):
+        assert g.tobytes() == wnt.tobytes()
+    if dtype == "f32":
+        omega = cf.cf_stage_grad_sqnorm(c, [cf.Stage(c, a)]).cpu().numpy()
+        ref = oracle.stage_grad_sqnorm(np_stage(a))
+        assert abs(omega[0] - ref) <= NORM_RTOL * ref
+    assert c.read_flags() == 0
 
 
 @pytest.mark.parametrize("dtype", ["f32", "bf16"])
