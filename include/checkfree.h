@@ -145,13 +145,13 @@ CF_API uint32_t cf_stage_num_chunks(const cf_stage *stage);
  *   d_omega_out  DEVICE array of n_stages doubles, written by the kernel
  *
  * Elements are squared and accumulated in binary32 per lane, reduced per
- * wavefront to one binary32 partial per (chunk, wavefront) at a fixed slot, and
- * the partials of a stage are summed in binary64 in a fixed order by a second,
+ * wavefront and then per workgroup (through LDS) to one binary32 partial per
+ * chunk at a fixed slot, and the partials of a stage are summed in binary64 in a fixed order by a second,
  * tiny kernel enqueued right behind the first: the result is bit-identical from
  * run to run and does not depend on the grid size.  An empty stage gives 0.  A non-finite result
  * raises CF_FLAG_NONFINITE_OMEGA.  The same stage handle must not appear in two
  * sqnorm calls that run concurrently (each handle owns its partial-sum scratch:
- * 16 bytes per chunk, allocated by cf_stage_create).
+ * 4 bytes per chunk, allocated by cf_stage_create).
  * Errors: CF_ERR_NULL, CF_ERR_DTYPE, CF_ERR_CONTEXT, CF_ERR_LIMIT, CF_ERR_HIP. */
 CF_API cf_status cf_stage_grad_sqnorm(cf_ctx *ctx, const cf_stage *const *grad_stages, uint32_t n_stages,
                                double *d_omega_out, void *stream);

@@ -14,8 +14,8 @@
 
 namespace {
 
-constexpr uint32_t kDefaultChunkBytes = 128u << 10;   // 32 tiles of 4 KiB
-constexpr uint32_t kMinChunkBytes = CF_TILE_BYTES;
+constexpr uint32_t kDefaultChunkBytes = 128u << 10;   // 128 tiles of 1 KiB
+constexpr uint32_t kMinChunkBytes = 4096;
 constexpr uint32_t kMaxChunkBytes = 4u << 20;
 constexpr uint32_t kDefaultSqnormBlocksPerCu = 0;     // 0: one workgroup per chunk
 constexpr uint64_t kMaxChunksPerStage = 1ull << 31;
@@ -53,7 +53,7 @@ struct cf_stage {
     uint32_t n_chunks = 0;
     bool all_f32 = true;
     CfChunk *d_chunks = nullptr;   // n_chunks entries
-    float *d_partials = nullptr;   // n_chunks * CF_WAVES floats (sqnorm scratch)
+    float *d_partials = nullptr;   // n_chunks floats (sqnorm scratch)
 };
 
 namespace {
@@ -347,9 +347,9 @@ cf_status cf_stage_create(cf_ctx *ctx, const cf_tensor *tensors, uint32_t num_te
         DeviceGuard guard(ctx->device);
         void *p = nullptr, *q = nullptr;
         bool ok = guard.ok() && hipMalloc(&p, n_chunks * sizeof(CfChunk)) == hipSuccess;
-        ok = ok && hipMalloc(&q, n_chunks * CF_WAVES * sizeof(float)) == hipSuccess;
+        ok = ok && hipMalloc(&q, n_chunks * sizeof(float)) == hipSuccess;
         ok = ok && hipMemcpy(p, table.data(), n_chunks * sizeof(CfChunk), hipMemcpyHostToDevice) == hipSuccess;
-        ok = ok && hipMemset(q, 0, n_chunks * CF_WAVES * sizeof(float)) == hipSuccess;
+        ok = ok && hipMemset(q, 0, n_chunks * sizeof(float)) == hipSuccess;
         ok = ok && hipDeviceSynchronize() == hipSuccess;
         if (!ok) {
             if (p) (void)hipFree(p);

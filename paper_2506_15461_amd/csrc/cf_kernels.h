@@ -17,18 +17,19 @@ struct CfChunk {
     uint32_t dtype;  // CF_F32 / CF_BF16
 };
 
-constexpr int CF_THREADS = 256;          // workgroup size of the streaming kernels: 4 wavefronts
+constexpr int CF_THREADS = 256;          // workgroup size of the norm's first pass: 4 wavefronts
 constexpr int CF_WAVES = CF_THREADS / 64;
 constexpr int CF_FINALIZE_THREADS = 1024;   // workgroup size of the norm's second pass
 constexpr int CF_MAX_SEG = 64;           // stages per sqnorm launch
-constexpr uint32_t CF_TILE_BYTES = CF_THREADS * 16u;   // one 16-byte vector per lane: the blend/copy work unit
+constexpr int CF_TILE_THREADS = 64;      // blend/copy: one wavefront per workgroup
+constexpr uint32_t CF_TILE_BYTES = CF_TILE_THREADS * 16u;   // one 16-byte vector per lane: the blend/copy work unit
 
 // Device word block owned by a context.
 constexpr int CF_WORD_FLAGS = 1;         // sticky CF_FLAG_* bits
 
 struct CfSqnormSeg {
     const CfChunk *chunks;   // the stage's chunk table
-    float *partials;         // CF_WAVES slots per chunk
+    float *partials;         // one slot per chunk
     uint32_t chunk_begin;    // index of the stage's first chunk in the launch
     uint32_t n_chunks;
 };

@@ -125,26 +125,36 @@ __device__ __forceinline__ float chunk_sqsum_f32(gcf32 p, uint32_t len, uint32_t
     return (a0 + a1) + (a2 + a3);
 }
 
-// First pass.  Workgroup b takes chunks b, b + grid, b + 2 grid, ...  Each
-// wavefront writes the sum of squares of its lanes' share of a chunk to slot
-// (chunk, wavefront) of the owning stage's partial array, so the partials do not
-// depend on the grid size.  There is no fence and no atomic on this streaming
-// pass: on this chip an agent-scope release per workgroup (an L2 write-back)
-// cuts a read-only stream to under 40 % of what it reaches without.
+// First pass.  Workgroup b takes chunks b, b + grid, b + 2 grid, ... (by default
+// the grid has one workgroup per chunk).  The four wavefront sums of a chunk
+// meet in LDS and leave as ONE binary32 partial at slot `chunk` of the owning
+// stage's partial array, so the partials do not depend on the grid size.  There
+// is no fence and no atomic on this streaming pass: on this chip an agent-scope
+// release per workgroup (an L2 write-back) cuts a read-only stream to under
+// 40 % of what it reaches without.
 __global__ __launch_bounds__(CF_THREADS) void cf_sqnorm_partials_kernel(CfSqnormArgs args)
 {
+    __shared__ float wave_part[2][CF_WAVES];
     const uint32_t tid = threadIdx.x;
     const uint32_t wave = tid >> 6;
     const uint32_t lane = tid & 63u;
 
     uint32_t s = 0;
+    uint32_t parity = 0;
     for (uint32_t c = blockIdx.x; c < args.total_chunks; c += gridDim.x) {
         while (s + 1 < args.n_seg && c >= args.seg[s + 1].chunk_begin) ++s;
         const uint32_t local = c - args.seg[s].chunk_begin;
         const CfChunk ch = args.seg[s].chunks[local];
         float t = chunk_sqsum_f32<8>((gcf32)ch.addr, ch.len, tid);
         float w = wave_sum(t);
-        if (lane == 0) args.seg[s].partials[(uint64_t)local * CF_WAVES + wave] = w;
+        // Two LDS rows used alternately: one barrier per chunk is enough, because a
+        // row is rewritten only after the barrier of the chunk in between.
+        if (lane == 0) wave_part[parity][wave] = w;
+        __syncthreads();
+        if (tid == 0)
+            args.seg[s].partials[local] =
+                (wave_part[parity][0] + wave_part[parity][1]) + (wave_part[parity][2] + wave_part[parity][3]);
+        parity ^= 1u;
     }
 }
 
@@ -157,7 +167,7 @@ __global__ __launch_bounds__(CF_FINALIZE_THREADS) void cf_sqnorm_finalize_kernel
     const uint32_t tid = threadIdx.x;
     const uint32_t k = blockIdx.x;
     const float *part = args.seg[k].partials;
-    const uint64_t np = (uint64_t)args.seg[k].n_chunks * CF_WAVES;
+    const uint64_t np = args.seg[k].n_chunks;
     double acc = 0.0;
     for (uint64_t i = tid; i < np; i += CF_FINALIZE_THREADS) acc += (double)part[i];
     red[tid] = acc;
@@ -226,13 +236,14 @@ __device__ __forceinline__ uint32_t blend_bf16_pair(const BlendWeights &w, uint3
     return lo | (hi << 16);
 }
 
-// One workgroup blends one *tile*: 256 sixteen-byte vectors of each of the three
-// streams, one vector per lane.  Workgroups are dispatched in tile order, so at
-// any moment the chip reads two narrow moving windows and writes a third; on
-// this memory system that ordering sustains about a fifth more bandwidth for a
-// two-read-one-write stream than a resident grid striding over large chunks.
-// Tile 0 of a chunk also takes the few elements before and after the 16-byte
-// aligned body.
+// One single-wavefront workgroup blends one *tile*: 64 sixteen-byte vectors of
+// each of the three streams, one vector per lane.  Workgroups are dispatched in
+// tile order, so at any moment the chip reads two narrow moving windows and
+// writes a third, and a compute unit takes a new tile whenever one wavefront
+// slot frees up; on this memory system that sustains about a quarter more
+// bandwidth for a two-read-one-write stream than a resident grid of 256-thread
+// workgroups striding over large chunks.  Tile 0 of a chunk also takes the few
+// elements before and after the 16-byte aligned body.
 __device__ __forceinline__ void blend_tile_f32(const BlendWeights &w, gcf32 pa, gcf32 pb, gf32 po, uint32_t len,
                                                uint32_t tile, uint32_t tid)
 {
@@ -241,7 +252,7 @@ __device__ __forceinline__ void blend_tile_f32(const BlendWeights &w, gcf32 pa, 
         // The three tensors sit differently inside their 16-byte lines: dword path.
 #pragma unroll
         for (uint32_t j = 0; j < 4; ++j) {
-            const uint32_t i = tile * (4u * CF_THREADS) + j * CF_THREADS + tid;
+            const uint32_t i = tile * (4u * CF_TILE_THREADS) + j * CF_TILE_THREADS + tid;
             if (i < len) po[i] = blend_to_f32(w, pa[i], pb[i]);
         }
         return;
@@ -249,7 +260,7 @@ __device__ __forceinline__ void blend_tile_f32(const BlendWeights &w, gcf32 pa, 
     const uint32_t head = head_elems((uint64_t)pa, 4u, len);
     const uint32_t rem = len - head;
     const uint32_t n4 = rem >> 2;
-    const uint32_t v = tile * CF_THREADS + tid;
+    const uint32_t v = tile * CF_TILE_THREADS + tid;
     if (v < n4) {
         const f32x4 a = __builtin_nontemporal_load((gcf32x4)(pa + head) + v);
         const f32x4 b = __builtin_nontemporal_load((gcf32x4)(pb + head) + v);
@@ -280,7 +291,7 @@ __device__ __forceinline__ void blend_tile_bf16(const BlendWeights &w, gcu16 pa,
     if (mis != (uint32_t)((uint64_t)pb & 15u) || mis != (uint32_t)((uint64_t)po & 15u)) {
 #pragma unroll
         for (uint32_t j = 0; j < 8; ++j) {
-            const uint32_t i = tile * (8u * CF_THREADS) + j * CF_THREADS + tid;
+            const uint32_t i = tile * (8u * CF_TILE_THREADS) + j * CF_TILE_THREADS + tid;
             if (i < len) po[i] = blend_to_bf16(w, pa[i], pb[i]);
         }
         return;
@@ -288,7 +299,7 @@ __device__ __forceinline__ void blend_tile_bf16(const BlendWeights &w, gcu16 pa,
     const uint32_t head = head_elems((uint64_t)pa, 2u, len);
     const uint32_t rem = len - head;
     const uint32_t n8 = rem >> 3;
-    const uint32_t v = tile * CF_THREADS + tid;
+    const uint32_t v = tile * CF_TILE_THREADS + tid;
     if (v < n8) {
         const u32x4 a = __builtin_nontemporal_load((gcu32x4)(pa + head) + v);
         const u32x4 b = __builtin_nontemporal_load((gcu32x4)(pb + head) + v);
@@ -312,7 +323,7 @@ __device__ __forceinline__ void blend_tile_bf16(const BlendWeights &w, gcu16 pa,
 // at once.  The norm-to-weight scaling is the kernel's prologue: every
 // workgroup reads the two binary64 omegas from device memory and derives
 // identical weights (the division overlaps the tile's loads).
-__global__ __launch_bounds__(CF_THREADS) void cf_blend_kernel(const CfChunk *prev, const CfChunk *next,
+__global__ __launch_bounds__(CF_TILE_THREADS) void cf_blend_kernel(const CfChunk *prev, const CfChunk *next,
                                                               const CfChunk *lost, uint32_t tile_shift,
                                                               const double *d_omega_prev,
                                                               const double *d_omega_next, uint32_t *words)
@@ -350,7 +361,7 @@ __global__ __launch_bounds__(CF_THREADS) void cf_blend_kernel(const CfChunk *pre
 // Bit-exact multi-tensor copy (CheckFree+): same tile-per-workgroup walk.
 // ---------------------------------------------------------------------------
 
-__global__ __launch_bounds__(CF_THREADS) void cf_copy_kernel(const CfChunk *src, const CfChunk *dst,
+__global__ __launch_bounds__(CF_TILE_THREADS) void cf_copy_kernel(const CfChunk *src, const CfChunk *dst,
                                                              uint32_t tile_shift)
 {
     const uint32_t tid = threadIdx.x;
@@ -370,7 +381,7 @@ __global__ __launch_bounds__(CF_THREADS) void cf_copy_kernel(const CfChunk *src,
             gu32 d4 = (gu32)pd;
 #pragma unroll
             for (uint32_t j = 0; j < 4; ++j) {
-                const uint32_t i = tile * (4u * CF_THREADS) + j * CF_THREADS + tid;
+                const uint32_t i = tile * (4u * CF_TILE_THREADS) + j * CF_TILE_THREADS + tid;
                 if (i < cd.len) d4[i] = s4[i];
             }
         } else {
@@ -378,7 +389,7 @@ __global__ __launch_bounds__(CF_THREADS) void cf_copy_kernel(const CfChunk *src,
             gu16 d2 = (gu16)pd;
 #pragma unroll
             for (uint32_t j = 0; j < 8; ++j) {
-                const uint32_t i = tile * (8u * CF_THREADS) + j * CF_THREADS + tid;
+                const uint32_t i = tile * (8u * CF_TILE_THREADS) + j * CF_TILE_THREADS + tid;
                 if (i < cd.len) d2[i] = s2[i];
             }
         }
@@ -387,7 +398,7 @@ __global__ __launch_bounds__(CF_THREADS) void cf_copy_kernel(const CfChunk *src,
     const uint32_t head = head_elems((uint64_t)ps, 1u, nbytes);
     const uint32_t rem = nbytes - head;
     const uint32_t n16 = rem >> 4;
-    const uint32_t v = tile * CF_THREADS + tid;
+    const uint32_t v = tile * CF_TILE_THREADS + tid;
     if (v < n16) __builtin_nontemporal_store(__builtin_nontemporal_load((gcu32x4)(ps + head) + v), (gu32x4)(pd + head) + v);
     if (tile == 0) {
         if (tid < head) pd[tid] = ps[tid];
@@ -414,7 +425,7 @@ hipError_t cf_launch_blend(const CfChunk *prev, const CfChunk *next, const CfChu
                            uint32_t tile_shift, const double *d_omega_prev, const double *d_omega_next,
                            uint32_t *words, hipStream_t stream)
 {
-    hipLaunchKernelGGL(cf_blend_kernel, dim3(n_chunks << tile_shift), dim3(CF_THREADS), 0, stream, prev, next, lost,
+    hipLaunchKernelGGL(cf_blend_kernel, dim3(n_chunks << tile_shift), dim3(CF_TILE_THREADS), 0, stream, prev, next, lost,
                        tile_shift, d_omega_prev, d_omega_next, words);
     return hipGetLastError();
 }
@@ -422,7 +433,7 @@ hipError_t cf_launch_blend(const CfChunk *prev, const CfChunk *next, const CfChu
 hipError_t cf_launch_copy(const CfChunk *src, const CfChunk *dst, uint32_t n_chunks, uint32_t tile_shift,
                           hipStream_t stream)
 {
-    hipLaunchKernelGGL(cf_copy_kernel, dim3(n_chunks << tile_shift), dim3(CF_THREADS), 0, stream, src, dst,
+    hipLaunchKernelGGL(cf_copy_kernel, dim3(n_chunks << tile_shift), dim3(CF_TILE_THREADS), 0, stream, src, dst,
                        tile_shift);
     return hipGetLastError();
 }
