@@ -30,6 +30,10 @@ def parse():
     p.add_argument("--config", type=int, default=3, help="workload 1..5 (3 = the 1.5B-shape stage the metric is quoted on)")
     p.add_argument("--no-cpu-baseline", action="store_true")
     p.add_argument("--cpu-seconds", type=float, default=15.0, help="target CPU time of the oracle baseline")
+    p.add_argument("--shape", type=str, default=None, help="override the stage shape: d,ffn,layers (exploration only)")
+    p.add_argument("--sets", type=int, default=0,
+                   help="independent buffer sets rotated step by step so that no step finds its inputs in the "
+                        "256 MB Infinity Cache (0 = enough sets to cover 1.5 GB)")
     return p.parse_args()
 
 
@@ -53,30 +57,27 @@ def main():
     dev = torch.device("cuda", 0)
     torch.cuda.set_device(dev)
     spec = workloads.SPECS[args.config]
-    wl = workloads.make_workload(args.config, device=dev, with_grads=args.config != 4)
+    shape = None
+    if args.shape:
+        d, ffn, layers = (int(x) for x in args.shape.split(","))
+        shape = workloads.StageShape(d, ffn, layers)
     ctx = cf.Context(0)
     stream = torch.cuda.current_stream()
 
-    numel = spec.shape.numel()
-    wbytes = 2 if spec.param_dtype == "bf16" else 4
+    def build_set(wl):
+        """Stage handles and the step closure for one set of buffers."""
+        if args.config == 4:
+            src_t = wl.weights[0] + wl.extra
+            dst_t = [torch.full_like(t, float("nan")) for t in src_t]
+            src, dst = cf.Stage(ctx, src_t), cf.Stage(ctx, dst_t)
 
-    if args.config == 4:
-        src_t = wl.weights[0] + wl.extra
-        dst_t = [torch.full_like(t, float("nan")) for t in src_t]
-        src, dst = cf.Stage(ctx, src_t), cf.Stage(ctx, dst_t)
-        copy_bytes = 2 * src.nbytes
-        step_bytes = copy_bytes
-        kernels = ["copy"]
-
-        def step(ev=None):
-            if ev:
-                ev[0].record(stream)
-            cf.cf_copy_stage(ctx, src, dst, stream)
-            if ev:
-                ev[1].record(stream)
-        kernel_bytes = {"copy": copy_bytes}
-        dominant = "copy"
-    else:
+            def step(ev=None):
+                if ev:
+                    ev[0].record(stream)
+                cf.cf_copy_stage(ctx, src, dst, stream)
+                if ev:
+                    ev[1].record(stream)
+            return step, {"copy": 2 * src.nbytes}, (src, dst, dst_t)
         if args.config == 5:
             lost = wl.lost
             grad_stages = [cf.Stage(ctx, g) for g in wl.grads]
@@ -88,10 +89,6 @@ def main():
         prev, nxt, out = (cf.Stage(ctx, wl.weights[i]) for i in (lost - 1, lost + 1, lost))
         omega = torch.zeros(len(grad_stages), dtype=torch.float64, device=dev)
         w_prev, w_next = omega[ip:ip + 1], omega[inx:inx + 1]
-        sq_bytes = sum(g.nbytes for g in grad_stages)
-        blend_bytes = 3 * out.nbytes
-        step_bytes = sq_bytes + blend_bytes
-        kernels = ["sqnorm", "blend"]
 
         def step(ev=None):
             if ev:
@@ -102,18 +99,38 @@ def main():
             cf.cf_recover_stage_weighted_avg(ctx, prev, nxt, w_prev, w_next, out, stream)
             if ev:
                 ev[2].record(stream)
-        kernel_bytes = {"sqnorm": sq_bytes, "blend": blend_bytes}
-        dominant = "blend"
+        return step, {"sqnorm": sum(g.nbytes for g in grad_stages), "blend": 3 * out.nbytes}, (grad_stages, prev, nxt, out, omega)
 
-    for _ in range(args.warmup):
-        step()
+    wl = workloads.make_workload(args.config, device=dev, shape=shape, with_grads=args.config != 4)
+    spec = wl.spec
+    numel = spec.shape.numel()
+    step0, kernel_bytes, keep0 = build_set(wl)
+    step_bytes = sum(kernel_bytes.values())
+    kernels = list(kernel_bytes)
+    dominant = "copy" if args.config == 4 else "blend"
+    # Rotate over enough independent buffer sets that a step never finds its
+    # inputs in the 256 MB Infinity Cache left there by the step before.
+    n_sets = args.sets if args.sets > 0 else max(1, -(-int(1.5e9) // step_bytes))
+    steps_fn, keep = [step0], [keep0, wl]
+    for i in range(1, n_sets):
+        wl_i = workloads.make_workload(args.config, device=dev, shape=shape, seed=spec.seed + 1000 * i,
+                                       with_grads=args.config != 4)
+        st, _, kp = build_set(wl_i)
+        steps_fn.append(st)
+        keep += [kp, wl_i]
+
+    def step(k, ev=None):
+        steps_fn[k % n_sets](ev)
+
+    for k in range(args.warmup):
+        step(k)
     torch.cuda.synchronize()
 
     events = [[torch.cuda.Event(enable_timing=True) for _ in range(len(kernels) + 1)] for _ in range(args.steps)]
     torch.cuda.synchronize()
     t0 = time.perf_counter()
     for k in range(args.steps):
-        step(events[k])
+        step(k, events[k])
     torch.cuda.synchronize()
     t1 = time.perf_counter()
     ms_per_step = (t1 - t0) * 1e3 / args.steps
@@ -148,6 +165,7 @@ def main():
             "step": "+".join(kernels),
             "algorithmic_bytes_per_step": int(step_bytes),
             "frac_of_hbm_peak": round(gbps / HBM_PEAK_GBPS, 4),
+            "buffer_sets_rotated": n_sets,
             "device_flags": flags,
         },
         "kernels": {name: {"ms_avg": round(v["avg"], 5), "ms_median": round(v["median"], 5),

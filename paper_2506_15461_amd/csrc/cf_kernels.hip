@@ -206,22 +206,25 @@ __device__ __forceinline__ float blend_to_f32(const BlendWeights &w, float a, fl
     return (float)blend_f64(w, (double)a, (double)b);
 }
 
-// binary64 -> bfloat16 bits in ONE rounding to nearest even: first to binary32
-// with round-to-odd (truncate, then make the last bit sticky), then the usual
-// nearest-even cut to the upper 16 bits.  binary32 carries more than two extra
-// bits over bfloat16, so the two steps equal a single correct rounding.
+// binary64 -> bfloat16 bits in ONE rounding to nearest even.  Narrowing to
+// binary32 first and cutting that to its upper 16 bits gives the same result
+// as the direct rounding unless the binary32 value lands exactly on a bfloat16
+// tie (low half 0x8000) that x itself is not on: every bfloat16 rounding
+// boundary is a binary32 number and rounding is monotone, so only then can the
+// first rounding have moved x onto the boundary.  In that rare case the
+// binary32 value is nudged one ulp back toward x before the cut.
 __device__ __forceinline__ uint32_t f64_to_bf16_bits(double x)
 {
-    if (x != x) return 0x7FC0u;
-    float f = (float)x;
+    const float f = (float)x;
     uint32_t u = __float_as_uint(f);
-    double back = (double)f;
-    if (back != x) {
-        if (__builtin_fabs(back) > __builtin_fabs(x)) u -= 1u;   // undo a round away from zero
-        u |= 1u;
+    if ((u & 0xFFFFu) == 0x8000u) {
+        const double back = __builtin_fabs((double)f);
+        const double ax = __builtin_fabs(x);
+        if (back > ax) u -= 1u;
+        else if (back < ax) u += 1u;
     }
     u += 0x7FFFu + ((u >> 16) & 1u);
-    return u >> 16;
+    return (x != x) ? 0x7FC0u : (u >> 16);
 }
 
 __device__ __forceinline__ double bf16_bits_to_f64(uint32_t h)
