@@ -141,7 +141,7 @@ CF_API uint32_t cf_stage_num_chunks(const cf_stage *stage);
  * all stages (groups of at most 64 stages per launch) plus its second pass.  Paper: section "CheckFree: Memoryless Recovery",
  * omega_i = ||grad W^S_i||^2; Algorithm 1, the two "Receive" steps.
  *
- *   grad_stages  HOST array of n_stages stage handles (all tensors CF_F32)
+ *   grad_stages  HOST array of n_stages stage handles (tensors CF_F32 or CF_BF16)
  *   d_omega_out  DEVICE array of n_stages doubles, written by the kernel
  *
  * Elements are squared and accumulated in binary32 per lane, reduced per
@@ -152,7 +152,7 @@ CF_API uint32_t cf_stage_num_chunks(const cf_stage *stage);
  * raises CF_FLAG_NONFINITE_OMEGA.  The same stage handle must not appear in two
  * sqnorm calls that run concurrently (each handle owns its partial-sum scratch:
  * 4 bytes per chunk, allocated by cf_stage_create).
- * Errors: CF_ERR_NULL, CF_ERR_DTYPE, CF_ERR_CONTEXT, CF_ERR_LIMIT, CF_ERR_HIP. */
+ * Errors: CF_ERR_NULL, CF_ERR_CONTEXT, CF_ERR_LIMIT, CF_ERR_HIP. */
 CF_API cf_status cf_stage_grad_sqnorm(cf_ctx *ctx, const cf_stage *const *grad_stages, uint32_t n_stages,
                                double *d_omega_out, void *stream);
 
@@ -181,6 +181,18 @@ CF_API cf_status cf_stage_grad_sqnorm(cf_ctx *ctx, const cf_stage *const *grad_s
 CF_API cf_status cf_recover_stage_weighted_avg(cf_ctx *ctx, const cf_stage *prev, const cf_stage *next,
                                         const double *d_omega_prev, const double *d_omega_next,
                                         cf_stage *lost, void *stream);
+
+/* The same recovery with the two weights given by the HOST, for the strategies
+ * the paper compares the gradient-norm weighting with (section "Motivation",
+ * the re-initialisation figure; section "CheckFree: Memoryless Recovery"):
+ *   omega_prev = omega_next (any positive value)   uniform average of the neighbours
+ *   omega_next = 0, omega_prev > 0                 copy of the previous stage
+ *   omega_prev = 0, omega_next > 0                 copy of the next stage
+ * and for callers that keep their omegas on the host.  Arithmetic, degenerate
+ * rule, flags, aliasing rules and errors as for cf_recover_stage_weighted_avg. */
+CF_API cf_status cf_recover_stage_with_weights(cf_ctx *ctx, const cf_stage *prev, const cf_stage *next,
+                                               double omega_prev, double omega_next, cf_stage *lost,
+                                               void *stream);
 
 /* Copies every tensor of src into the corresponding tensor of dst, bit for bit
  * (NaN payloads, signed zeros and subnormals included); bytes outside dst's
@@ -212,6 +224,12 @@ CF_API uint64_t cf_plan_num_chunks(const cf_tensor *tensors, uint32_t num_tensor
  * CF_ERR_LIMIT if cap is too small. */
 CF_API cf_status cf_plan_chunks(const cf_tensor *tensors, uint32_t num_tensors, uint32_t chunk_bytes,
                          uint32_t *chunk_tensor, uint64_t *chunk_first, uint32_t *chunk_len, uint64_t cap);
+
+/* Learning rate of a stage that has just been recovered: the paper scales the
+ * stage's current rate up by 1.1 (Algorithm 1, third step; the scheduler then
+ * carries on from there).  Pure host arithmetic. */
+#define CF_RECOVERY_LR_FACTOR 1.1
+CF_API double cf_recovered_learning_rate(double learning_rate);
 
 /* The tuning values in effect when `tuning` is NULL or holds zeros. */
 CF_API void cf_default_tuning(cf_tuning *out);

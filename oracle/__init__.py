@@ -36,6 +36,8 @@ def _lib():
         c_dp = ctypes.POINTER(ctypes.c_double)
         lib.cfo_sqnorm_f32.restype = ctypes.c_double
         lib.cfo_sqnorm_f32.argtypes = [ctypes.c_void_p, ctypes.c_uint64]
+        lib.cfo_sqnorm_bf16.restype = ctypes.c_double
+        lib.cfo_sqnorm_bf16.argtypes = [ctypes.c_void_p, ctypes.c_uint64]
         lib.cfo_stage_sqnorm_f32.restype = ctypes.c_double
         lib.cfo_stage_sqnorm_f32.argtypes = [ctypes.c_void_p, ctypes.c_void_p, ctypes.c_uint32]
         lib.cfo_stage_sqnorm_f32_mt.restype = ctypes.c_double
@@ -78,7 +80,19 @@ def _flat(a, dtype):
 
 def stage_grad_sqnorm(grads, threads: int = 1) -> float:
     """omega of one stage: sum over its tensors (list order) of the sum of
-    squares of every fp32 gradient element, accumulated in binary64."""
+    squares of every gradient element, accumulated in binary64.  Gradients are
+    fp32 in every workload; a stage holding bf16 gradients (uint16 bit
+    patterns) is summed tensor by tensor in the same way."""
+    if any(np.asarray(g).dtype == np.uint16 for g in grads):
+        omega = 0.0
+        for g in grads:
+            g = np.ascontiguousarray(g)
+            if g.dtype == np.uint16:
+                omega += float(_lib().cfo_sqnorm_bf16(g.ctypes.data, g.size))
+            else:
+                g = _flat(g, np.float32)
+                omega += float(_lib().cfo_sqnorm_f32(g.ctypes.data, g.size))
+        return omega
     arrs = [_flat(g, np.float32) for g in grads]
     n = len(arrs)
     ptrs = (ctypes.c_void_p * max(n, 1))(*[a.ctypes.data for a in arrs])

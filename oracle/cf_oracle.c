@@ -64,6 +64,19 @@ double cfo_sqnorm_f32(const float *g, uint64_t n)
     return acc;
 }
 
+static double bf16_to_f64(uint16_t h);
+
+/* Sum of squares of one bfloat16 tensor (bit patterns), elements in index order. */
+double cfo_sqnorm_bf16(const uint16_t *g, uint64_t n)
+{
+    double acc = 0.0;
+    for (uint64_t k = 0; k < n; ++k) {
+        double v = bf16_to_f64(g[k]);
+        acc += v * v;
+    }
+    return acc;
+}
+
 /* omega of a stage: the tensors' sums of squares added in list order. */
 double cfo_stage_sqnorm_f32(const float *const *tensors, const uint64_t *numel,
                             uint32_t num_tensors)

@@ -35,6 +35,7 @@ EXPORTS = (
     "cf_stage_num_tensors", "cf_stage_numel", "cf_stage_nbytes", "cf_stage_num_chunks",
     "cf_stage_grad_sqnorm", "cf_recover_stage_weighted_avg", "cf_copy_stage", "cf_read_flags",
     "cf_plan_num_chunks", "cf_plan_chunks", "cf_default_tuning", "cf_status_string",
+    "cf_recover_stage_with_weights", "cf_recovered_learning_rate",
 )
 
 
@@ -93,6 +94,10 @@ def load_library():
     lib.cf_stage_grad_sqnorm.argtypes = [vp, ctypes.POINTER(vp), u32, vp, vp]
     lib.cf_recover_stage_weighted_avg.restype = i32
     lib.cf_recover_stage_weighted_avg.argtypes = [vp, vp, vp, vp, vp, vp, vp]
+    lib.cf_recover_stage_with_weights.restype = i32
+    lib.cf_recover_stage_with_weights.argtypes = [vp, vp, vp, ctypes.c_double, ctypes.c_double, vp, vp]
+    lib.cf_recovered_learning_rate.restype = ctypes.c_double
+    lib.cf_recovered_learning_rate.argtypes = [ctypes.c_double]
     lib.cf_copy_stage.restype = i32
     lib.cf_copy_stage.argtypes = [vp, vp, vp, vp]
     lib.cf_read_flags.restype = i32
@@ -258,6 +263,21 @@ def cf_recover_stage_weighted_avg(ctx: Context, prev: Stage, next: Stage, omega_
         ctx._h, prev._h, next._h, _omega_ptr(ctx, omega_prev), _omega_ptr(ctx, omega_next), lost._h,
         _stream_ptr(stream)), "cf_recover_stage_weighted_avg")
     return lost
+
+
+def cf_recover_stage_with_weights(ctx: Context, prev: Stage, next: Stage, omega_prev: float, omega_next: float,
+                                  lost: Stage, stream=None):
+    """The recovery with host-supplied weights (uniform average: equal weights;
+    copy of one neighbour: zero weight on the other).  Asynchronous."""
+    _check(load_library().cf_recover_stage_with_weights(
+        ctx._h, prev._h, next._h, float(omega_prev), float(omega_next), lost._h, _stream_ptr(stream)),
+        "cf_recover_stage_with_weights")
+    return lost
+
+
+def cf_recovered_learning_rate(learning_rate: float) -> float:
+    """1.1 x the stage's current learning rate (Algorithm 1, third step)."""
+    return float(load_library().cf_recovered_learning_rate(float(learning_rate)))
 
 
 def cf_copy_stage(ctx: Context, src: Stage, dst: Stage, stream=None):

@@ -51,7 +51,6 @@ struct cf_stage {
     uint64_t numel = 0;
     uint64_t nbytes = 0;
     uint32_t n_chunks = 0;
-    bool all_f32 = true;
     CfChunk *d_chunks = nullptr;   // n_chunks entries
     float *d_partials = nullptr;   // n_chunks floats (sqnorm scratch)
 };
@@ -333,7 +332,6 @@ cf_status cf_stage_create(cf_ctx *ctx, const cf_tensor *tensors, uint32_t num_te
         stage->tensors.push_back(h);
         stage->numel += d.numel;
         stage->nbytes += d.numel * elem_size(d.dtype);
-        if (d.dtype != CF_F32) stage->all_f32 = false;
         const uint64_t chunk_elems = chunk_bytes / elem_size(d.dtype);
         for (uint64_t first = 0; first < d.numel; first += chunk_elems) {
             CfChunk c;
@@ -391,7 +389,6 @@ cf_status cf_stage_grad_sqnorm(cf_ctx *ctx, const cf_stage *const *grad_stages, 
     for (uint32_t s = 0; s < n_stages; ++s) {
         if (!grad_stages[s]) return CF_ERR_NULL;
         if (grad_stages[s]->ctx != ctx) return CF_ERR_CONTEXT;
-        if (!grad_stages[s]->all_f32) return CF_ERR_DTYPE;
     }
     DeviceGuard guard(ctx->device);
     if (!guard.ok()) return CF_ERR_HIP;
@@ -419,11 +416,13 @@ cf_status cf_stage_grad_sqnorm(cf_ctx *ctx, const cf_stage *const *grad_stages, 
     return CF_OK;
 }
 
-cf_status cf_recover_stage_weighted_avg(cf_ctx *ctx, const cf_stage *prev, const cf_stage *next,
-                                        const double *d_omega_prev, const double *d_omega_next,
-                                        cf_stage *lost, void *stream)
+namespace {
+
+cf_status recover_impl(cf_ctx *ctx, const cf_stage *prev, const cf_stage *next, const double *d_omega_prev,
+                       const double *d_omega_next, double h_omega_prev, double h_omega_next, cf_stage *lost,
+                       void *stream)
 {
-    if (!ctx || !prev || !next || !lost || !d_omega_prev || !d_omega_next) return CF_ERR_NULL;
+    if (!ctx || !prev || !next || !lost) return CF_ERR_NULL;
     if (prev->ctx != ctx || next->ctx != ctx || lost->ctx != ctx) return CF_ERR_CONTEXT;
     cf_status st = checked_pair(ctx, prev, lost);
     if (st != CF_OK) return st;
@@ -433,10 +432,29 @@ cf_status cf_recover_stage_weighted_avg(cf_ctx *ctx, const cf_stage *prev, const
     DeviceGuard guard(ctx->device);
     if (!guard.ok()) return CF_ERR_HIP;
     if (cf_launch_blend(prev->d_chunks, next->d_chunks, lost->d_chunks, lost->n_chunks, ctx->tile_shift,
-                        d_omega_prev, d_omega_next, ctx->d_words, static_cast<hipStream_t>(stream)) != hipSuccess)
+                        d_omega_prev, d_omega_next, h_omega_prev, h_omega_next, ctx->d_words,
+                        static_cast<hipStream_t>(stream)) != hipSuccess)
         return CF_ERR_HIP;
     return CF_OK;
 }
+
+}  // namespace
+
+cf_status cf_recover_stage_weighted_avg(cf_ctx *ctx, const cf_stage *prev, const cf_stage *next,
+                                        const double *d_omega_prev, const double *d_omega_next,
+                                        cf_stage *lost, void *stream)
+{
+    if (!d_omega_prev || !d_omega_next) return CF_ERR_NULL;
+    return recover_impl(ctx, prev, next, d_omega_prev, d_omega_next, 0.0, 0.0, lost, stream);
+}
+
+cf_status cf_recover_stage_with_weights(cf_ctx *ctx, const cf_stage *prev, const cf_stage *next,
+                                        double omega_prev, double omega_next, cf_stage *lost, void *stream)
+{
+    return recover_impl(ctx, prev, next, nullptr, nullptr, omega_prev, omega_next, lost, stream);
+}
+
+double cf_recovered_learning_rate(double learning_rate) { return CF_RECOVERY_LR_FACTOR * learning_rate; }
 
 cf_status cf_copy_stage(cf_ctx *ctx, const cf_stage *src, cf_stage *dst, void *stream)
 {

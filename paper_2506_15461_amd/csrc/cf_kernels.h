@@ -46,9 +46,10 @@ struct CfSqnormArgs {
 hipError_t cf_launch_sqnorm(const CfSqnormArgs &args, uint32_t grid, hipStream_t stream);
 
 // One workgroup per tile; a chunk holds at most 2^tile_shift tiles of CF_TILE_BYTES.
+// The weights are read from d_omega_* when those are non-null, else taken from h_omega_*.
 hipError_t cf_launch_blend(const CfChunk *prev, const CfChunk *next, const CfChunk *lost, uint32_t n_chunks,
                            uint32_t tile_shift, const double *d_omega_prev, const double *d_omega_next,
-                           uint32_t *words, hipStream_t stream);
+                           double h_omega_prev, double h_omega_next, uint32_t *words, hipStream_t stream);
 
 hipError_t cf_launch_copy(const CfChunk *src, const CfChunk *dst, uint32_t n_chunks, uint32_t tile_shift,
                           hipStream_t stream);

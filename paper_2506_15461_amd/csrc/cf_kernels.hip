@@ -125,6 +125,56 @@ __device__ __forceinline__ float chunk_sqsum_f32(gcf32 p, uint32_t len, uint32_t
     return (a0 + a1) + (a2 + a3);
 }
 
+// The same for a bfloat16 chunk: eight elements per 16-byte vector, widened to
+// binary32 (exact), squared and accumulated in binary32.
+template <int kUnroll>
+__device__ __forceinline__ float chunk_sqsum_bf16(gcu16 p, uint32_t len, uint32_t tid)
+{
+    float a0 = 0.f, a1 = 0.f, a2 = 0.f, a3 = 0.f;
+    const uint32_t head = head_elems((uint64_t)p, 2u, len);
+    if (tid < head) {
+        float v = __uint_as_float((uint32_t)p[tid] << 16);
+        a0 = __builtin_fmaf(v, v, a0);
+    }
+    gcu32x4 q = (gcu32x4)(p + head);
+    const uint32_t rem = len - head;
+    const uint32_t n8 = rem >> 3;
+#define CF_SQ_BF16_WORD(word, lo_acc, hi_acc)                 \
+    {                                                          \
+        const float lo = __uint_as_float((word) << 16);        \
+        const float hi = __uint_as_float((word) & 0xFFFF0000u); \
+        lo_acc = __builtin_fmaf(lo, lo, lo_acc);               \
+        hi_acc = __builtin_fmaf(hi, hi, hi_acc);               \
+    }
+    uint32_t i = tid;
+    for (; i + (kUnroll - 1) * CF_THREADS < n8; i += kUnroll * CF_THREADS) {
+        u32x4 v[kUnroll];
+#pragma unroll
+        for (int u = 0; u < kUnroll; ++u) v[u] = __builtin_nontemporal_load(q + i + u * CF_THREADS);
+#pragma unroll
+        for (int u = 0; u < kUnroll; ++u) {
+            CF_SQ_BF16_WORD(v[u].x, a0, a1)
+            CF_SQ_BF16_WORD(v[u].y, a2, a3)
+            CF_SQ_BF16_WORD(v[u].z, a0, a1)
+            CF_SQ_BF16_WORD(v[u].w, a2, a3)
+        }
+    }
+    for (; i < n8; i += CF_THREADS) {
+        const u32x4 v = __builtin_nontemporal_load(q + i);
+        CF_SQ_BF16_WORD(v.x, a0, a1)
+        CF_SQ_BF16_WORD(v.y, a2, a3)
+        CF_SQ_BF16_WORD(v.z, a0, a1)
+        CF_SQ_BF16_WORD(v.w, a2, a3)
+    }
+#undef CF_SQ_BF16_WORD
+    const uint32_t tail = rem & 7u;
+    if (tid < tail) {
+        float v = __uint_as_float((uint32_t)p[head + (n8 << 3) + tid] << 16);
+        a0 = __builtin_fmaf(v, v, a0);
+    }
+    return (a0 + a1) + (a2 + a3);
+}
+
 // First pass.  Workgroup b takes chunks b, b + grid, b + 2 grid, ... (by default
 // the grid has one workgroup per chunk).  The four wavefront sums of a chunk
 // meet in LDS and leave as ONE binary32 partial at slot `chunk` of the owning
@@ -145,7 +195,8 @@ __global__ __launch_bounds__(CF_THREADS) void cf_sqnorm_partials_kernel(CfSqnorm
         while (s + 1 < args.n_seg && c >= args.seg[s + 1].chunk_begin) ++s;
         const uint32_t local = c - args.seg[s].chunk_begin;
         const CfChunk ch = args.seg[s].chunks[local];
-        float t = chunk_sqsum_f32<8>((gcf32)ch.addr, ch.len, tid);
+        float t = (ch.dtype == kDtypeF32) ? chunk_sqsum_f32<8>((gcf32)ch.addr, ch.len, tid)
+                                          : chunk_sqsum_bf16<8>((gcu16)ch.addr, ch.len, tid);
         float w = wave_sum(t);
         // Two LDS rows used alternately: one barrier per chunk is enough, because a
         // row is rewritten only after the barrier of the chunk in between.
@@ -326,10 +377,14 @@ __device__ __forceinline__ void blend_tile_bf16(const BlendWeights &w, gcu16 pa,
 // at once.  The norm-to-weight scaling is the kernel's prologue: every
 // workgroup reads the two binary64 omegas from device memory and derives
 // identical weights (the division overlaps the tile's loads).
+//
+// The omegas come from device memory (d_omega_* non-null: the norms never visit
+// the host) or, for the ablation variants with explicit weights, by value.
 __global__ __launch_bounds__(CF_TILE_THREADS) void cf_blend_kernel(const CfChunk *prev, const CfChunk *next,
                                                               const CfChunk *lost, uint32_t tile_shift,
                                                               const double *d_omega_prev,
-                                                              const double *d_omega_next, uint32_t *words)
+                                                              const double *d_omega_next, double h_omega_prev,
+                                                              double h_omega_next, uint32_t *words)
 {
     const uint32_t tid = threadIdx.x;
     const uint32_t c = blockIdx.x >> tile_shift;
@@ -340,8 +395,8 @@ __global__ __launch_bounds__(CF_TILE_THREADS) void cf_blend_kernel(const CfChunk
     const CfChunk cb = next[c];
 
     BlendWeights w;
-    w.wp = *d_omega_prev;
-    w.wn = *d_omega_next;
+    w.wp = d_omega_prev ? *d_omega_prev : h_omega_prev;
+    w.wn = d_omega_next ? *d_omega_next : h_omega_next;
     double den = w.wp + w.wn;
     // Usable pair: both finite and non-negative, sum a positive normal number.
     const bool usable = (w.wp - w.wp == 0.0) && (w.wn - w.wn == 0.0) && w.wp >= 0.0 && w.wn >= 0.0 &&
@@ -426,10 +481,10 @@ hipError_t cf_launch_sqnorm(const CfSqnormArgs &args, uint32_t grid, hipStream_t
 
 hipError_t cf_launch_blend(const CfChunk *prev, const CfChunk *next, const CfChunk *lost, uint32_t n_chunks,
                            uint32_t tile_shift, const double *d_omega_prev, const double *d_omega_next,
-                           uint32_t *words, hipStream_t stream)
+                           double h_omega_prev, double h_omega_next, uint32_t *words, hipStream_t stream)
 {
     hipLaunchKernelGGL(cf_blend_kernel, dim3(n_chunks << tile_shift), dim3(CF_TILE_THREADS), 0, stream, prev, next, lost,
-                       tile_shift, d_omega_prev, d_omega_next, words);
+                       tile_shift, d_omega_prev, d_omega_next, h_omega_prev, h_omega_next, words);
     return hipGetLastError();
 }
 

@@ -125,3 +125,11 @@ def test_context_creation_fails_cleanly_without_a_gpu(lib):
     with pytest.raises(cf.CheckFreeError) as e:
         cf.Context(0)
     assert e.value.status == cf.CF_ERR_HIP
+
+
+def test_recovered_learning_rate(lib):
+    # Algorithm 1, third step: lambda_i <- 1.1 lambda_i
+    assert cf.cf_recovered_learning_rate(1.0) == 1.1
+    assert cf.cf_recovered_learning_rate(3e-4) == 1.1 * 3e-4
+    assert cf.cf_recovered_learning_rate(0.0) == 0.0
+    assert lib.cf_recover_stage_with_weights(None, None, None, 1.0, 1.0, None, None) == cf.CF_ERR_NULL

@@ -145,11 +145,15 @@ def test_sqnorm_more_stages_than_one_launch_holds(ctx, dev):
     assert np.array_equal(omega, 4.0 * np.arange(1, 71))
 
 
-def test_sqnorm_rejects_bf16_gradients(ctx, dev):
-    st = cf.Stage(ctx, [torch.ones(8, device=dev, dtype=torch.bfloat16)])
-    with pytest.raises(cf.CheckFreeError) as e:
-        cf.cf_stage_grad_sqnorm(ctx, [st])
-    assert e.value.status == cf.CF_ERR_DTYPE
+def test_sqnorm_bf16_gradients(ctx, dev):
+    gen = torch.Generator(device=dev).manual_seed(17)
+    shapes = workloads.ragged_shapes(8) + [(300_001,)]
+    g16 = [torch.empty(s, device=dev).normal_(0, 1e-3, generator=gen).to(torch.bfloat16) for s in shapes]
+    mixed = [g16[0], torch.empty(70_001, device=dev).normal_(0, 1e-3, generator=gen), g16[-1][5:]]
+    omega = cf.cf_stage_grad_sqnorm(ctx, [cf.Stage(ctx, g16), cf.Stage(ctx, mixed)]).cpu().numpy()
+    for k, st in enumerate((g16, mixed)):
+        ref = oracle.stage_grad_sqnorm(np_stage(st))
+        assert abs(omega[k] - ref) <= NORM_RTOL * ref, (k, omega[k], ref)
 
 
 # ----------------------------------------------------------------------------
@@ -222,6 +226,30 @@ def test_blend_special_cases_are_exact(ctx, dev, dtype):
     w = _omega(dev, 3.7e-3, 1.9e-2)                  # identical neighbours give back that stage
     cf.cf_recover_stage_weighted_avg(ctx, sa, sa, w[0:1], w[1:2], so)
     assert same(out, a)
+
+
+@pytest.mark.parametrize("dtype", ["f32", "bf16"])
+def test_recovery_with_host_weights_matches_device_weights_and_oracle(ctx, dev, dtype):
+    """The strategies the paper compares: uniform average, copy of one neighbour,
+    and explicit weights; the host-weight entry point must give the same bits as
+    the device-weight one."""
+    shapes = workloads.ragged_shapes(6)
+    a, b = _draw_pair(dev, shapes, dtype, 41)
+    out_h = [torch.full_like(t, float("nan")) for t in a]
+    out_d = [torch.full_like(t, float("nan")) for t in a]
+    sa, sb, sh, sd = cf.Stage(ctx, a), cf.Stage(ctx, b), cf.Stage(ctx, out_h), cf.Stage(ctx, out_d)
+    bits = torch.int32 if dtype == "f32" else torch.int16
+    for wp, wn in [(1.0, 1.0), (0.37, 0.37), (1.0, 0.0), (0.0, 1.0), (3.7e-3, 1.9e-2)]:
+        cf.cf_recover_stage_with_weights(ctx, sa, sb, wp, wn, sh)
+        w = _omega(dev, wp, wn)
+        cf.cf_recover_stage_weighted_avg(ctx, sa, sb, w[0:1], w[1:2], sd)
+        torch.cuda.synchronize()
+        assert all(torch.equal(x.view(bits), y.view(bits)) for x, y in zip(out_h, out_d))
+        assert_blend_close(np_stage(out_h), oracle.recover_stage_weighted_avg(np_stage(a), np_stage(b), wp, wn))
+        if wn == 0.0:
+            assert all(torch.equal(x.view(bits), y.view(bits)) for x, y in zip(out_h, a))      # copy previous
+        if wp == 0.0:
+            assert all(torch.equal(x.view(bits), y.view(bits)) for x, y in zip(out_h, b))
 
 
 def test_blend_misaligned_and_in_place(ctx, dev):

@@ -112,3 +112,24 @@ def test_statistical_expectation_at_model_shape():
         mean = float(np.sum(n * wl.sigmas[s] ** 2))
         sd = float(np.sqrt(np.sum(2 * n * wl.sigmas[s] ** 4)))
         assert abs(oracle.stage_grad_sqnorm(grads) - mean) < 6 * sd
+
+
+def test_bf16_gradients_closed_form_and_exact_rational():
+    # bf16 bit patterns: 0x3C00 = 2^-7; the ramp 1..256 is exact in bf16
+    c = np.full(1000, 0x3C00, dtype=np.uint16)
+    assert oracle.stage_grad_sqnorm([c]) == 1000 * 2.0 ** -14
+    ramp32 = np.arange(1, 257, dtype=np.float32)
+    ramp = (ramp32.view(np.uint32) >> 16).astype(np.uint16)
+    assert np.all((ramp.astype(np.uint32) << 16).view(np.float32) == ramp32)
+    assert oracle.stage_grad_sqnorm([ramp]) == 256 * 257 * 513 // 6
+    rng = np.random.default_rng(3)
+    bits = rng.integers(0, 0x7F80, 300).astype(np.uint16) | (rng.integers(0, 2, 300).astype(np.uint16) << 15)
+    vals = (bits.astype(np.uint32) << 16).view(np.float32)
+    keep = np.abs(vals) < 1e10
+    bits = bits[keep]
+    exact = sum(Fraction(float(v)) ** 2 for v in (bits.astype(np.uint32) << 16).view(np.float32))
+    got = Fraction(oracle.stage_grad_sqnorm([bits]))
+    assert abs(got - exact) <= exact * Fraction(1, 10 ** 15)
+    # mixed stage: fp32 and bf16 tensors add up
+    f = np.array([3.0, 4.0], np.float32)
+    assert oracle.stage_grad_sqnorm([f, c]) == 25.0 + 1000 * 2.0 ** -14
