@@ -21,6 +21,21 @@ if ROOT not in sys.path:
 
 HBM_PEAK_GBPS = 8000.0          # MI355X HBM3E, vendor figure
 
+# HBM bytes per launch from rocprofv3 FETCH_SIZE / WRITE_SIZE counters, each scaled by what the same
+# counter reads for the copy kernel of known size (profiles/cf_kernels_hbm_traffic_pmc.md).  Valid only
+# for the kernel sources they were taken on: reported as null once those have changed.
+TRAFFIC_KERNEL_SHA256 = "26c8093317318af125c600dacf331b5f6b34c2ef021e1ba23065fe9923a8ed61"
+TRAFFIC_BYTES_PER_LAUNCH = {(3, "cf_blend_kernel"): 2464886000}
+
+
+def kernel_sources_sha256():
+    import hashlib
+    h = hashlib.sha256()
+    for name in ("cf_kernels.hip", "cf_kernels.h"):
+        with open(os.path.join(ROOT, "paper_2506_15461_amd", "csrc", name), "rb") as f:
+            h.update(f.read())
+    return h.hexdigest()
+
 
 def parse():
     p = argparse.ArgumentParser()
@@ -144,6 +159,11 @@ def main():
     dom_ms = kernel_ms[dominant]["avg"]
     achieved = kernel_bytes[dominant] / (dom_ms * 1e-3) / 1e9
 
+    dominant_kernel = {"blend": "cf_blend_kernel", "copy": "cf_copy_kernel"}[dominant]
+    traffic = None
+    if not args.shape and kernel_sources_sha256() == TRAFFIC_KERNEL_SHA256:
+        traffic = TRAFFIC_BYTES_PER_LAUNCH.get((args.config, dominant_kernel))
+
     result = {
         "metric": "stage_recovery_hbm_throughput",
         "value": round(gbps, 1),
@@ -173,13 +193,14 @@ def main():
                            "GBps_avg": round(kernel_bytes[name] / (v["avg"] * 1e-3) / 1e9, 1)}
                     for name, v in kernel_ms.items()},
         "roofline": {
-            "kernel": {"blend": "cf_blend_kernel", "copy": "cf_copy_kernel"}[dominant],
+            "kernel": dominant_kernel,
             "bound": "hbm",
             "achieved": round(achieved, 1),
             "peak": HBM_PEAK_GBPS,
             "unit": "GB/s",
             "frac": round(achieved / HBM_PEAK_GBPS, 4),
-            "traffic": None,
+            "traffic": traffic,
+            "algorithmic_bytes_per_launch": int(kernel_bytes[dominant]),
         },
     }
 
