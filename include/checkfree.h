@@ -225,6 +225,16 @@ CF_API uint64_t cf_plan_num_chunks(const cf_tensor *tensors, uint32_t num_tensor
 CF_API cf_status cf_plan_chunks(const cf_tensor *tensors, uint32_t num_tensors, uint32_t chunk_bytes,
                          uint32_t *chunk_tensor, uint64_t *chunk_first, uint32_t *chunk_len, uint64_t cap);
 
+/* The check cf_recover_stage_* and cf_copy_stage apply to an (input stage, output
+ * stage) pair, on bare descriptors: every descriptor valid (CF_ERR_DTYPE,
+ * CF_ERR_NULL, CF_ERR_ALIGN, CF_ERR_LIMIT), same tensor count, numel and dtype
+ * tensor by tensor (CF_ERR_SHAPE_MISMATCH), no output tensor sharing a byte with
+ * any input tensor except its own counterpart at exactly the same address, and
+ * no two output tensors sharing a byte (CF_ERR_ALIAS).  Pointers are compared,
+ * never dereferenced. */
+CF_API cf_status cf_check_stage_pair(const cf_tensor *in, uint32_t num_in, const cf_tensor *out,
+                                     uint32_t num_out);
+
 /* Learning rate of a stage that has just been recovered: the paper scales the
  * stage's current rate up by 1.1 (Algorithm 1, third step; the scheduler then
  * carries on from there).  Pure host arithmetic. */

@@ -31,7 +31,9 @@ _LIB = None
 def _lib():
     global _LIB
     if _LIB is None:
-        path = build_oracle.build(force=False)
+        # CF_ORACLE_LIB: a differently built copy of the oracle; used only by the mutation
+        # tests, which check that the pins reject deliberately broken oracles.
+        path = os.environ.get("CF_ORACLE_LIB") or build_oracle.build(force=False)
         lib = ctypes.CDLL(path)
         c_dp = ctypes.POINTER(ctypes.c_double)
         lib.cfo_sqnorm_f32.restype = ctypes.c_double

@@ -35,7 +35,7 @@ EXPORTS = (
     "cf_stage_num_tensors", "cf_stage_numel", "cf_stage_nbytes", "cf_stage_num_chunks",
     "cf_stage_grad_sqnorm", "cf_recover_stage_weighted_avg", "cf_copy_stage", "cf_read_flags",
     "cf_plan_num_chunks", "cf_plan_chunks", "cf_default_tuning", "cf_status_string",
-    "cf_recover_stage_with_weights", "cf_recovered_learning_rate",
+    "cf_recover_stage_with_weights", "cf_recovered_learning_rate", "cf_check_stage_pair",
 )
 
 
@@ -107,6 +107,8 @@ def load_library():
     lib.cf_plan_chunks.restype = i32
     lib.cf_plan_chunks.argtypes = [ctypes.POINTER(CfTensor), u32, u32, ctypes.POINTER(u32),
                                    ctypes.POINTER(u64), ctypes.POINTER(u32), u64]
+    lib.cf_check_stage_pair.restype = i32
+    lib.cf_check_stage_pair.argtypes = [ctypes.POINTER(CfTensor), u32, ctypes.POINTER(CfTensor), u32]
     lib.cf_default_tuning.restype = None
     lib.cf_default_tuning.argtypes = [ctypes.POINTER(CfTuning)]
     lib.cf_status_string.restype = ctypes.c_char_p
@@ -284,6 +286,19 @@ def cf_copy_stage(ctx: Context, src: Stage, dst: Stage, stream=None):
     """dst <- src bit for bit (CheckFree+ end-stage / (de)embedding recovery)."""
     _check(load_library().cf_copy_stage(ctx._h, src._h, dst._h, _stream_ptr(stream)), "cf_copy_stage")
     return dst
+
+
+def check_stage_pair(inputs, outputs) -> int:
+    """Host-only: status of the (input, output) congruence and aliasing check for
+    descriptor lists given as (address, numel, dtype) triples."""
+    def pack(items):
+        arr = (CfTensor * max(len(items), 1))()
+        for i, (addr, numel, dtype) in enumerate(items):
+            arr[i].data = addr or None
+            arr[i].numel = int(numel)
+            arr[i].dtype = int(dtype)
+        return arr
+    return int(load_library().cf_check_stage_pair(pack(inputs), len(inputs), pack(outputs), len(outputs)))
 
 
 def plan_chunks(numels, chunk_bytes, dtype=CF_F32):

@@ -100,19 +100,18 @@ struct Range {
 };
 
 // `out` may coincide with `in` tensor for tensor; any other shared byte is an error.
-cf_status check_pair(const cf_stage *in, const cf_stage *out)
+cf_status check_pair(const std::vector<HostTensor> &in, const std::vector<HostTensor> &out)
 {
-    if (in->tensors.size() != out->tensors.size()) return CF_ERR_SHAPE_MISMATCH;
-    const size_t n = in->tensors.size();
+    if (in.size() != out.size()) return CF_ERR_SHAPE_MISMATCH;
+    const size_t n = in.size();
     for (size_t t = 0; t < n; ++t) {
-        if (in->tensors[t].numel != out->tensors[t].numel || in->tensors[t].dtype != out->tensors[t].dtype)
-            return CF_ERR_SHAPE_MISMATCH;
+        if (in[t].numel != out[t].numel || in[t].dtype != out[t].dtype) return CF_ERR_SHAPE_MISMATCH;
     }
     // Sweep over the input ranges sorted by address; for each output range look at its neighbours.
     std::vector<Range> rin;
     rin.reserve(n);
     for (size_t t = 0; t < n; ++t) {
-        const HostTensor &h = in->tensors[t];
+        const HostTensor &h = in[t];
         if (h.numel) rin.push_back({h.addr, h.addr + h.numel * elem_size(h.dtype), (uint32_t)t});
     }
     std::sort(rin.begin(), rin.end(), [](const Range &x, const Range &y) { return x.lo < y.lo; });
@@ -124,7 +123,7 @@ cf_status check_pair(const cf_stage *in, const cf_stage *out)
         max_hi[i] = m;
     }
     for (size_t t = 0; t < n; ++t) {
-        const HostTensor &o = out->tensors[t];
+        const HostTensor &o = out[t];
         if (!o.numel) continue;
         const uint64_t lo = o.addr, hi = o.addr + o.numel * elem_size(o.dtype);
         // first input range with lo >= hi of the output: everything from there on is clear
@@ -142,11 +141,11 @@ cf_status check_pair(const cf_stage *in, const cf_stage *out)
 }
 
 // Output tensors must not overlap one another either (two writers of one byte).
-cf_status check_self(const cf_stage *out)
+cf_status check_self(const std::vector<HostTensor> &out)
 {
     std::vector<Range> r;
-    for (size_t t = 0; t < out->tensors.size(); ++t) {
-        const HostTensor &h = out->tensors[t];
+    for (size_t t = 0; t < out.size(); ++t) {
+        const HostTensor &h = out[t];
         if (h.numel) r.push_back({h.addr, h.addr + h.numel * elem_size(h.dtype), (uint32_t)t});
     }
     std::sort(r.begin(), r.end(), [](const Range &x, const Range &y) { return x.lo < y.lo; });
@@ -160,9 +159,9 @@ cf_status checked_pair(cf_ctx *ctx, const cf_stage *in, const cf_stage *out)
     const std::pair<uint64_t, uint64_t> key(in->id, out->id);
     if (std::find(ctx->checked.begin(), ctx->checked.end(), key) != ctx->checked.end()) return CF_OK;
     try {
-        cf_status st = check_pair(in, out);
+        cf_status st = check_pair(in->tensors, out->tensors);
         if (st != CF_OK) return st;
-        st = check_self(out);
+        st = check_self(out->tensors);
         if (st != CF_OK) return st;
         if (ctx->checked.size() >= 256) ctx->checked.erase(ctx->checked.begin());
         ctx->checked.push_back(key);
@@ -246,6 +245,29 @@ cf_status cf_plan_chunks(const cf_tensor *tensors, uint32_t num_tensors, uint32_
         }
     }
     return CF_OK;
+}
+
+cf_status cf_check_stage_pair(const cf_tensor *in, uint32_t num_in, const cf_tensor *out, uint32_t num_out)
+{
+    if ((num_in && !in) || (num_out && !out)) return CF_ERR_NULL;
+    try {
+        std::vector<HostTensor> vin, vout;
+        for (uint32_t t = 0; t < num_in; ++t) {
+            cf_status st = check_tensor(in[t]);
+            if (st != CF_OK) return st;
+            vin.push_back({reinterpret_cast<uint64_t>(in[t].data), in[t].numel, in[t].dtype});
+        }
+        for (uint32_t t = 0; t < num_out; ++t) {
+            cf_status st = check_tensor(out[t]);
+            if (st != CF_OK) return st;
+            vout.push_back({reinterpret_cast<uint64_t>(out[t].data), out[t].numel, out[t].dtype});
+        }
+        cf_status st = check_pair(vin, vout);
+        if (st != CF_OK) return st;
+        return check_self(vout);
+    } catch (...) {
+        return CF_ERR_LIMIT;   // host memory exhausted
+    }
 }
 
 cf_status cf_ctx_create(int device, const cf_tuning *tuning, cf_ctx **out)

@@ -133,3 +133,74 @@ def test_recovered_learning_rate(lib):
     assert cf.cf_recovered_learning_rate(3e-4) == 1.1 * 3e-4
     assert cf.cf_recovered_learning_rate(0.0) == 0.0
     assert lib.cf_recover_stage_with_weights(None, None, None, 1.0, 1.0, None, None) == cf.CF_ERR_NULL
+
+
+def test_stage_pair_check_shapes_and_dtypes(lib):
+    F, H = cf.CF_F32, cf.CF_BF16
+    A = [(0x1000, 100, F), (0x2000, 7, H), (0, 0, F)]
+    B = [(0x9000, 100, F), (0xA000, 7, H), (0, 0, F)]
+    assert cf.check_stage_pair(A, B) == cf.CF_OK
+    assert cf.check_stage_pair(A, B[:2]) == cf.CF_ERR_SHAPE_MISMATCH
+    assert cf.check_stage_pair(A, [(0x9000, 101, F)] + B[1:]) == cf.CF_ERR_SHAPE_MISMATCH
+    assert cf.check_stage_pair(A, [(0x9000, 100, H)] + B[1:]) == cf.CF_ERR_SHAPE_MISMATCH
+    assert cf.check_stage_pair(A, [(0x9000, 100, 5)] + B[1:]) == cf.CF_ERR_DTYPE
+    assert cf.check_stage_pair([(0x1002, 4, F)], [(0x9000, 4, F)]) == cf.CF_ERR_ALIGN      # fp32 at 2 mod 4
+    assert cf.check_stage_pair([(0x1001, 4, H)], [(0x9000, 4, H)]) == cf.CF_ERR_ALIGN
+    assert cf.check_stage_pair([(0x1002, 4, H)], [(0x9000, 4, H)]) == cf.CF_OK
+    assert cf.check_stage_pair([(0, 4, F)], [(0x9000, 4, F)]) == cf.CF_ERR_NULL
+    assert cf.check_stage_pair([], []) == cf.CF_OK
+
+
+def test_stage_pair_check_aliasing(lib):
+    F = cf.CF_F32
+    # identical memory, tensor for tensor: allowed (in-place recovery)
+    A = [(0x1000, 100, F), (0x2000, 50, F)]
+    assert cf.check_stage_pair(A, A) == cf.CF_OK
+    # same addresses but crossed over between tensors of equal size: output 0 overwrites input 1
+    assert cf.check_stage_pair([(0x1000, 100, F), (0x2000, 100, F)], [(0x2000, 100, F), (0x1000, 100, F)]) == cf.CF_ERR_ALIAS
+    # shifted overlap with its own counterpart
+    assert cf.check_stage_pair([(0x1000, 100, F)], [(0x1004, 100, F)]) == cf.CF_ERR_ALIAS
+    # touching but not overlapping: [0x1000, 0x1190) then 0x1190
+    assert cf.check_stage_pair([(0x1000, 100, F)], [(0x1190, 100, F)]) == cf.CF_OK
+    assert cf.check_stage_pair([(0x1000, 100, F)], [(0x118C, 100, F)]) == cf.CF_ERR_ALIAS   # last dword shared
+    # output inside a much larger input that starts far below it
+    big = [(0x10000, 1 << 20, F), (0x900000, 10, F)]
+    out = [(0xA00000, 1 << 20, F), (0x10000 + 4 * 5000, 10, F)]
+    assert cf.check_stage_pair(big, out) == cf.CF_ERR_ALIAS
+    # many small inputs after a large one: the sweep must still see the large one
+    ins = [(0x10000, 1 << 20, F)] + [(0x800000 + 0x100 * k, 8, F) for k in range(20)]
+    outs = [(0x2000000, 1 << 20, F)] + [(0x3000000 + 0x100 * k, 8, F) for k in range(19)] + [(0x10000 + 0x3FFF00, 8, F)]
+    assert cf.check_stage_pair(ins, outs) == cf.CF_ERR_ALIAS
+    outs[-1] = (0x10000 + 0x400000, 8, F)                      # first byte after the large input
+    assert cf.check_stage_pair(ins, outs) == cf.CF_OK
+    # two output tensors overlapping each other
+    assert cf.check_stage_pair([(0x1000, 10, F), (0x2000, 10, F)], [(0x9000, 10, F), (0x9020, 10, F)]) == cf.CF_ERR_ALIAS
+    assert cf.check_stage_pair([(0x1000, 10, F), (0x2000, 10, F)], [(0x9000, 10, F), (0x9028, 10, F)]) == cf.CF_OK
+    # empty tensors never alias
+    assert cf.check_stage_pair([(0x1000, 0, F), (0x1000, 4, F)], [(0x1000, 0, F), (0x1000, 4, F)]) == cf.CF_OK
+
+
+def test_stage_pair_check_against_brute_force(lib):
+    rng = np.random.default_rng(0)
+    F = cf.CF_F32
+    for trial in range(300):
+        n = int(rng.integers(1, 6))
+        sizes = rng.integers(1, 12, n)
+        ins = [(0x1000 + 4 * int(rng.integers(0, 60)), int(s), F) for s in sizes]
+        outs = [(0x1000 + 4 * int(rng.integers(0, 120)), int(s), F) for s in sizes]
+        if rng.random() < 0.3:
+            k = int(rng.integers(0, n))
+            outs[k] = ins[k]
+        def rng_of(t):
+            return range(t[0], t[0] + 4 * t[1])
+        bad = False
+        for i, o in enumerate(outs):
+            so = set(rng_of(o))
+            for j, a in enumerate(ins):
+                if so & set(rng_of(a)) and not (i == j and a[0] == o[0]):
+                    bad = True
+            for j, o2 in enumerate(outs):
+                if j != i and so & set(rng_of(o2)):
+                    bad = True
+        want = cf.CF_ERR_ALIAS if bad else cf.CF_OK
+        assert cf.check_stage_pair(ins, outs) == want, (ins, outs)

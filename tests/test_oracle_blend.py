@@ -124,6 +124,21 @@ def test_exact_rational_brute_force(dtype):
     assert off <= 2          # double rounding through binary64 is a ~1e-8 event per element
 
 
+def test_bf16_result_is_rounded_once_not_through_fp32():
+    """A value a hair above a bf16 tie: one rounding goes up; rounding to fp32
+    first lands on the tie and then goes to even (down).  a = 1, b = 1 + 2^-7,
+    weights 1 and 1 + 2^-20 give 1 + 2^-8 + about 2^-29."""
+    a = np.array([0x3F80], np.uint16)
+    b = np.array([0x3F81], np.uint16)
+    wp, wn = 1.0, 1.0 + 2.0 ** -20
+    exact = (Fraction(wp) * 1 + Fraction(wn) * (1 + Fraction(1, 128))) / (Fraction(wp) + Fraction(wn))
+    assert exact > 1 + Fraction(1, 256) and exact - (1 + Fraction(1, 256)) < Fraction(1, 2 ** 28)
+    assert em.fraction_to_bf16_bits(exact) == 0x3F81
+    assert oracle.recover_stage_weighted_avg([a], [b], wp, wn)[0][0] == 0x3F81
+    # mirrored: a hair below the tie goes down
+    assert oracle.recover_stage_weighted_avg([a], [b], wn, wp)[0][0] == 0x3F80
+
+
 def test_unrounded_value_matches_exact_rational():
     rng = np.random.default_rng(14)
     a = rng.normal(0, 0.02, 200).astype(np.float32).astype(np.float64)

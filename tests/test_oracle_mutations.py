@@ -1,0 +1,91 @@
+"""Do the pins bite?  Each mutant is the oracle's C source with one plausible
+mistake planted (on the CPU, in a temporary copy); the pin tests are run against
+it in a subprocess and must fail.  A mutant that survives means a hole in the
+pins."""
+import os
+import subprocess
+import sys
+from concurrent.futures import ThreadPoolExecutor
+
+import pytest
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+SRC = os.path.join(ROOT, "oracle", "cf_oracle.c")
+PIN_FILES = ["tests/test_oracle_sqnorm.py", "tests/test_oracle_blend.py", "tests/test_oracle_bf16_copy.py"]
+
+# (name, text in oracle/cf_oracle.c, replacement)
+MUTANTS = [
+    ("sqnorm: square dropped", "double v = (double)g[k];\n        acc += v * v;", "double v = (double)g[k];\n        acc += v;"),
+    ("sqnorm: absolute value instead of square", "double v = (double)g[k];\n        acc += v * v;",
+     "double v = (double)g[k];\n        acc += fabs(v);"),
+    ("sqnorm: last tensor of the stage left out", "for (uint32_t t = 0; t < num_tensors; ++t)\n        omega += cfo_sqnorm_f32",
+     "for (uint32_t t = 0; t + 1 < num_tensors; ++t)\n        omega += cfo_sqnorm_f32"),
+    ("sqnorm: threaded split loses the remainder", "uint64_t hi = (p == threads - 1) ? n : n / (uint64_t)threads * (uint64_t)(p + 1);\n            piece[p]",
+     "uint64_t hi = n / (uint64_t)threads * (uint64_t)(p + 1);\n            piece[p]"),
+    ("sqnorm bf16: square dropped", "double v = bf16_to_f64(g[k]);\n        acc += v * v;", "double v = bf16_to_f64(g[k]);\n        acc += v;"),
+    ("blend: weights swapped", "double numerator = wp * a + wn * b;", "double numerator = wn * a + wp * b;"),
+    ("blend: the algorithm box's misprint (omega_{i-1} on both terms)", "double numerator = wp * a + wn * b;",
+     "double numerator = wp * a + wp * b;"),
+    ("blend: second term dropped", "double numerator = wp * a + wn * b;", "double numerator = wp * a;"),
+    ("blend: difference instead of sum", "double numerator = wp * a + wn * b;", "double numerator = wp * a - wn * b;"),
+    ("blend: not normalised", "return numerator / denominator;", "return numerator;"),
+    ("blend: denominator without omega_{i+1}", "double denominator = wp + wn;", "double denominator = wp;"),
+    ("blend: unweighted mean whatever the omegas", "double numerator = wp * a + wn * b;\n    double denominator = wp + wn;",
+     "double numerator = a + b;\n    double denominator = 2.0;"),
+    ("blend f32: next read from prev", "blend_value(wp, wn, (double)prev[k], (double)next[k])", "blend_value(wp, wn, (double)prev[k], (double)prev[k])"),
+    ("blend f32: arithmetic in binary32", "out[k] = (float)blend_value(wp, wn, (double)prev[k], (double)next[k]);",
+     "out[k] = ((float)wp * prev[k] + (float)wn * next[k]) / ((float)wp + (float)wn);"),
+    ("blend bf16: rounded through binary32 first", "out[k] = f64_to_bf16(blend_value(",
+     "out[k] = f64_to_bf16((double)(float)blend_value("),
+    ("bf16: truncation instead of nearest-even", "double r = nearbyint(scaled);", "double r = floor(scaled);"),
+    ("bf16: ties away from zero", "double r = nearbyint(scaled);", "double r = floor(scaled + 0.5);"),
+    ("bf16: subnormals flushed", "if (E < -126) E = -126;", "if (E < -126) return sign;"),
+    ("bf16: widening shift off by one", "uint32_t w = (uint32_t)h << 16;", "uint32_t w = (uint32_t)h << 15;"),
+    ("weights: zero omega on one side treated as unusable", "omega_next >= 0.0 && isfinite(d)", "omega_next > 0.0 && isfinite(d)"),
+    ("weights: negative omega accepted", "omega_prev >= 0.0 &&", "1 &&"),
+    ("weights: zero sum accepted", "d >= 2.2250738585072014e-308", "d >= 0.0"),
+    ("copy: one byte short", "memcpy(dst, src, nbytes);\n        return;", "memcpy(dst, src, nbytes ? nbytes - 1 : 0);\n        return;"),
+]
+
+
+def _run_mutant(args):
+    idx, (name, old, new), tmp = args
+    src = open(SRC).read()
+    if src.count(old) < 1:
+        return name, "pattern not found in the oracle source"
+    mutated = src.replace(old, new, 1)
+    c_path = os.path.join(tmp, f"mutant{idx}.c")
+    so_path = os.path.join(tmp, f"mutant{idx}.so")
+    with open(c_path, "w") as f:
+        f.write(mutated)
+    cc = subprocess.run(["gcc", "-std=c11", "-O2", "-fPIC", "-shared", "-fopenmp", "-ffp-contract=off",
+                         c_path, "-o", so_path, "-lm"], capture_output=True, text=True)
+    if cc.returncode != 0:
+        return name, "mutant does not compile: " + cc.stderr[-300:]
+    env = dict(os.environ, CF_ORACLE_LIB=so_path, OMP_NUM_THREADS="2")
+    r = subprocess.run([sys.executable, "-m", "pytest", "-x", "-q", "-p", "no:cacheprovider", *PIN_FILES],
+                       cwd=ROOT, env=env, capture_output=True, text=True)
+    if r.returncode == 0:
+        return name, "SURVIVED: every pin passed"
+    if "passed" not in r.stdout and "failed" not in r.stdout:
+        return name, "pin run broke instead of failing: " + (r.stdout + r.stderr)[-300:]
+    return name, None
+
+
+def test_unmutated_oracle_passes_through_the_same_harness(tmp_path):
+    # the harness itself: the pristine source, built the same way, passes
+    so_path = str(tmp_path / "pristine.so")
+    subprocess.run(["gcc", "-std=c11", "-O2", "-fPIC", "-shared", "-fopenmp", "-ffp-contract=off", SRC, "-o", so_path,
+                    "-lm"], check=True)
+    env = dict(os.environ, CF_ORACLE_LIB=so_path, OMP_NUM_THREADS="2")
+    r = subprocess.run([sys.executable, "-m", "pytest", "-x", "-q", "-p", "no:cacheprovider", *PIN_FILES], cwd=ROOT,
+                       env=env, capture_output=True, text=True)
+    assert r.returncode == 0, r.stdout[-500:]
+
+
+def test_every_planted_mistake_is_caught(tmp_path):
+    jobs = [(i, m, str(tmp_path)) for i, m in enumerate(MUTANTS)]
+    with ThreadPoolExecutor(max_workers=4) as pool:
+        results = list(pool.map(_run_mutant, jobs))
+    problems = [f"{name}: {why}" for name, why in results if why]
+    assert not problems, "\n".join(problems)
