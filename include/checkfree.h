@@ -156,6 +156,23 @@ CF_API uint32_t cf_stage_num_chunks(const cf_stage *stage);
 CF_API cf_status cf_stage_grad_sqnorm(cf_ctx *ctx, const cf_stage *const *grad_stages, uint32_t n_stages,
                                double *d_omega_out, void *stream);
 
+/* omega of ONE stage and, alongside, the squared norm of each of its tensors
+ * (what a gradient-clipping or monitoring pass wants from the same read of the
+ * gradients): the streaming pass of cf_stage_grad_sqnorm runs once, then two
+ * independent second passes add its per-chunk partials per stage and per tensor.
+ *
+ *   d_tensor_sqnorm  DEVICE array of cf_stage_num_tensors(grad_stage) doubles
+ *   d_omega_out      DEVICE, one double; bit-identical to what
+ *                    cf_stage_grad_sqnorm writes for the same stage
+ *
+ * The per-tensor values are each a fixed-order binary64 sum of that tensor's
+ * partials; their sum equals omega up to binary64 rounding, not bit for bit.
+ * (If the stage holds only empty tensors the zeros are written with
+ * hipMemsetAsync; do not capture that case into a HIP graph.)
+ * Errors: CF_ERR_NULL, CF_ERR_CONTEXT, CF_ERR_LIMIT, CF_ERR_HIP. */
+CF_API cf_status cf_stage_grad_sqnorm_per_tensor(cf_ctx *ctx, const cf_stage *grad_stage,
+                                                 double *d_tensor_sqnorm, double *d_omega_out, void *stream);
+
 /* Rebuilds a lost intermediate stage from its two neighbours:
  *   lost[t][k] = (w_p * prev[t][k] + w_n * next[t][k]) / (w_p + w_n)
  * for every tensor t and element k, with w_p = *d_omega_prev, w_n = *d_omega_next

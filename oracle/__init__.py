@@ -104,6 +104,11 @@ def stage_grad_sqnorm(grads, threads: int = 1) -> float:
     return float(_lib().cfo_stage_sqnorm_f32_mt(ptrs, lens, n, int(threads)))
 
 
+def tensor_grad_sqnorms(grads):
+    """The squared norm of each tensor of a stage, in list order; omega is their sum."""
+    return [stage_grad_sqnorm([g]) for g in grads]
+
+
 def effective_omega(omega_prev: float, omega_next: float):
     """(w_prev, w_next, degenerate): the weights the blend really uses."""
     ep, en = ctypes.c_double(), ctypes.c_double()

@@ -36,6 +36,7 @@ EXPORTS = (
     "cf_stage_grad_sqnorm", "cf_recover_stage_weighted_avg", "cf_copy_stage", "cf_read_flags",
     "cf_plan_num_chunks", "cf_plan_chunks", "cf_default_tuning", "cf_status_string",
     "cf_recover_stage_with_weights", "cf_recovered_learning_rate", "cf_check_stage_pair",
+    "cf_stage_grad_sqnorm_per_tensor",
 )
 
 
@@ -92,6 +93,8 @@ def load_library():
     lib.cf_stage_num_chunks.argtypes = [vp]
     lib.cf_stage_grad_sqnorm.restype = i32
     lib.cf_stage_grad_sqnorm.argtypes = [vp, ctypes.POINTER(vp), u32, vp, vp]
+    lib.cf_stage_grad_sqnorm_per_tensor.restype = i32
+    lib.cf_stage_grad_sqnorm_per_tensor.argtypes = [vp, vp, vp, vp, vp]
     lib.cf_recover_stage_weighted_avg.restype = i32
     lib.cf_recover_stage_weighted_avg.argtypes = [vp, vp, vp, vp, vp, vp, vp]
     lib.cf_recover_stage_with_weights.restype = i32
@@ -248,6 +251,19 @@ def cf_stage_grad_sqnorm(ctx: Context, grad_stages, out=None, stream=None):
     _check(load_library().cf_stage_grad_sqnorm(ctx._h, handles, n, ctypes.c_void_p(out.data_ptr()),
                                                _stream_ptr(stream)), "cf_stage_grad_sqnorm")
     return out
+
+
+def cf_stage_grad_sqnorm_per_tensor(ctx: Context, grad_stage: Stage, stream=None):
+    """(omega, per-tensor squared norms) of one stage as float64 device tensors
+    of 1 and len(tensors) elements.  Asynchronous on the stream."""
+    import torch
+    n = len(grad_stage.tensors)
+    omega = torch.empty(1, dtype=torch.float64, device=ctx.device)
+    per_tensor = torch.empty(n, dtype=torch.float64, device=ctx.device)
+    _check(load_library().cf_stage_grad_sqnorm_per_tensor(
+        ctx._h, grad_stage._h, ctypes.c_void_p(per_tensor.data_ptr() if n else None),
+        ctypes.c_void_p(omega.data_ptr()), _stream_ptr(stream)), "cf_stage_grad_sqnorm_per_tensor")
+    return omega, per_tensor
 
 
 def _omega_ptr(ctx, w):

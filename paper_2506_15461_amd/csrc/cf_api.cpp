@@ -53,6 +53,7 @@ struct cf_stage {
     uint32_t n_chunks = 0;
     CfChunk *d_chunks = nullptr;   // n_chunks entries
     float *d_partials = nullptr;   // n_chunks floats (sqnorm scratch)
+    uint32_t *d_tensor_first = nullptr;   // tensors + 1 entries: first chunk of each tensor
 };
 
 namespace {
@@ -341,8 +342,10 @@ cf_status cf_stage_create(cf_ctx *ctx, const cf_tensor *tensors, uint32_t num_te
     stage->id = g_next_stage_id.fetch_add(1);
     stage->n_chunks = (uint32_t)n_chunks;
     std::vector<CfChunk> table;
+    std::vector<uint32_t> tensor_first;
     try {
         table.reserve(n_chunks);
+        tensor_first.reserve(num_tensors + 1);
         stage->tensors.reserve(num_tensors);
     } catch (...) {
         delete stage;
@@ -355,6 +358,7 @@ cf_status cf_stage_create(cf_ctx *ctx, const cf_tensor *tensors, uint32_t num_te
         stage->numel += d.numel;
         stage->nbytes += d.numel * elem_size(d.dtype);
         const uint64_t chunk_elems = chunk_bytes / elem_size(d.dtype);
+        tensor_first.push_back((uint32_t)table.size());
         for (uint64_t first = 0; first < d.numel; first += chunk_elems) {
             CfChunk c;
             c.addr = h.addr + first * elem_size(d.dtype);
@@ -363,10 +367,14 @@ cf_status cf_stage_create(cf_ctx *ctx, const cf_tensor *tensors, uint32_t num_te
             table.push_back(c);
         }
     }
+    tensor_first.push_back((uint32_t)table.size());
     if (n_chunks) {
         DeviceGuard guard(ctx->device);
-        void *p = nullptr, *q = nullptr;
+        void *p = nullptr, *q = nullptr, *r = nullptr;
         bool ok = guard.ok() && hipMalloc(&p, n_chunks * sizeof(CfChunk)) == hipSuccess;
+        ok = ok && hipMalloc(&r, tensor_first.size() * sizeof(uint32_t)) == hipSuccess;
+        ok = ok && hipMemcpy(r, tensor_first.data(), tensor_first.size() * sizeof(uint32_t),
+                             hipMemcpyHostToDevice) == hipSuccess;
         ok = ok && hipMalloc(&q, n_chunks * sizeof(float)) == hipSuccess;
         ok = ok && hipMemcpy(p, table.data(), n_chunks * sizeof(CfChunk), hipMemcpyHostToDevice) == hipSuccess;
         ok = ok && hipMemset(q, 0, n_chunks * sizeof(float)) == hipSuccess;
@@ -374,11 +382,13 @@ cf_status cf_stage_create(cf_ctx *ctx, const cf_tensor *tensors, uint32_t num_te
         if (!ok) {
             if (p) (void)hipFree(p);
             if (q) (void)hipFree(q);
+            if (r) (void)hipFree(r);
             delete stage;
             return CF_ERR_HIP;
         }
         stage->d_chunks = static_cast<CfChunk *>(p);
         stage->d_partials = static_cast<float *>(q);
+        stage->d_tensor_first = static_cast<uint32_t *>(r);
     }
     *out = stage;
     return CF_OK;
@@ -394,6 +404,7 @@ cf_status cf_stage_destroy(cf_stage *stage)
         if (!guard.ok()) st = CF_ERR_HIP;
         if (stage->d_chunks && hipFree(stage->d_chunks) != hipSuccess) st = CF_ERR_HIP;
         if (stage->d_partials && hipFree(stage->d_partials) != hipSuccess) st = CF_ERR_HIP;
+        if (stage->d_tensor_first && hipFree(stage->d_tensor_first) != hipSuccess) st = CF_ERR_HIP;
     }
     delete stage;
     return st;
@@ -435,6 +446,31 @@ cf_status cf_stage_grad_sqnorm(cf_ctx *ctx, const cf_stage *const *grad_stages, 
         const uint32_t grid = sqnorm_grid(ctx, args.total_chunks);
         if (cf_launch_sqnorm(args, grid, static_cast<hipStream_t>(stream)) != hipSuccess) return CF_ERR_HIP;
     }
+    return CF_OK;
+}
+
+cf_status cf_stage_grad_sqnorm_per_tensor(cf_ctx *ctx, const cf_stage *grad_stage, double *d_tensor_sqnorm,
+                                          double *d_omega_out, void *stream)
+{
+    if (!ctx || !grad_stage || !d_omega_out) return CF_ERR_NULL;
+    if (!grad_stage->tensors.empty() && !d_tensor_sqnorm) return CF_ERR_NULL;
+    const cf_stage *one[1] = {grad_stage};
+    cf_status st = cf_stage_grad_sqnorm(ctx, one, 1, d_omega_out, stream);
+    if (st != CF_OK) return st;
+    if (grad_stage->tensors.empty()) return CF_OK;
+    DeviceGuard guard(ctx->device);
+    if (!guard.ok()) return CF_ERR_HIP;
+    if (grad_stage->n_chunks == 0) {
+        // only empty tensors: their norms are zero; no partials exist to add up
+        if (hipMemsetAsync(d_tensor_sqnorm, 0, grad_stage->tensors.size() * sizeof(double),
+                           static_cast<hipStream_t>(stream)) != hipSuccess)
+            return CF_ERR_HIP;
+        return CF_OK;
+    }
+    if (cf_launch_sqnorm_tensors(grad_stage->d_partials, grad_stage->d_tensor_first,
+                                 (uint32_t)grad_stage->tensors.size(), d_tensor_sqnorm,
+                                 static_cast<hipStream_t>(stream)) != hipSuccess)
+        return CF_ERR_HIP;
     return CF_OK;
 }
 

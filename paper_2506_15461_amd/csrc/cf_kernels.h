@@ -45,6 +45,11 @@ struct CfSqnormArgs {
 // First pass over `grid` workgroups, then the fixed-order second pass (one workgroup per stage).
 hipError_t cf_launch_sqnorm(const CfSqnormArgs &args, uint32_t grid, hipStream_t stream);
 
+// Per-tensor second pass over a stage's partials (after cf_launch_sqnorm on the same stream):
+// tensor t owns chunks tensor_first_chunk[t] .. tensor_first_chunk[t+1]-1.
+hipError_t cf_launch_sqnorm_tensors(const float *partials, const uint32_t *tensor_first_chunk, uint32_t num_tensors,
+                                    double *d_tensor_out, hipStream_t stream);
+
 // One workgroup per tile; a chunk holds at most 2^tile_shift tiles of CF_TILE_BYTES.
 // The weights are read from d_omega_* when those are non-null, else taken from h_omega_*.
 hipError_t cf_launch_blend(const CfChunk *prev, const CfChunk *next, const CfChunk *lost, uint32_t n_chunks,

@@ -234,6 +234,27 @@ __global__ __launch_bounds__(CF_FINALIZE_THREADS) void cf_sqnorm_finalize_kernel
     }
 }
 
+// Second pass, per tensor: workgroup t adds the partials of the chunks of tensor
+// t (chunks first[t] .. first[t+1]-1 of the stage) in binary64 in a fixed order.
+__global__ __launch_bounds__(CF_THREADS) void cf_sqnorm_finalize_tensors_kernel(const float *partials,
+                                                                               const uint32_t *first,
+                                                                               double *tensor_out)
+{
+    __shared__ double red[CF_THREADS];
+    const uint32_t tid = threadIdx.x;
+    const uint32_t lo = first[blockIdx.x];
+    const uint32_t hi = first[blockIdx.x + 1];
+    double acc = 0.0;
+    for (uint32_t i = lo + tid; i < hi; i += CF_THREADS) acc += (double)partials[i];
+    red[tid] = acc;
+    __syncthreads();
+    for (uint32_t off = CF_THREADS / 2; off > 0; off >>= 1) {
+        if (tid < off) red[tid] += red[tid + off];
+        __syncthreads();
+    }
+    if (tid == 0) tensor_out[blockIdx.x] = red[0];
+}
+
 // ---------------------------------------------------------------------------
 // W_lost = (w_p W_prev + w_n W_next) / (w_p + w_n)
 // ---------------------------------------------------------------------------
@@ -476,6 +497,14 @@ hipError_t cf_launch_sqnorm(const CfSqnormArgs &args, uint32_t grid, hipStream_t
         if (e != hipSuccess) return e;
     }
     hipLaunchKernelGGL(cf_sqnorm_finalize_kernel, dim3(args.n_seg), dim3(CF_FINALIZE_THREADS), 0, stream, args);
+    return hipGetLastError();
+}
+
+hipError_t cf_launch_sqnorm_tensors(const float *partials, const uint32_t *tensor_first_chunk, uint32_t num_tensors,
+                                    double *d_tensor_out, hipStream_t stream)
+{
+    hipLaunchKernelGGL(cf_sqnorm_finalize_tensors_kernel, dim3(num_tensors), dim3(CF_THREADS), 0, stream, partials,
+                       tensor_first_chunk, d_tensor_out);
     return hipGetLastError();
 }
 

@@ -145,6 +145,28 @@ def test_sqnorm_more_stages_than_one_launch_holds(ctx, dev):
     assert np.array_equal(omega, 4.0 * np.arange(1, 71))
 
 
+def test_sqnorm_per_tensor(ctx, dev):
+    wl = workloads.make_workload(1, device=dev, shape=workloads.StageShape(192, 512, 2))
+    grads = wl.grads[0] + [torch.empty(0, device=dev), torch.full((5,), 2.0, device=dev)]
+    st = cf.Stage(ctx, grads)
+    omega, per = cf.cf_stage_grad_sqnorm_per_tensor(ctx, st)
+    omega2 = cf.cf_stage_grad_sqnorm(ctx, [st])
+    torch.cuda.synchronize()
+    assert omega.cpu().numpy().tobytes() == omega2.cpu().numpy().tobytes()       # same bits as the plain call
+    per = per.cpu().numpy()
+    ref = oracle.tensor_grad_sqnorms(np_stage(grads))
+    assert len(per) == len(ref) == 20
+    for t in range(len(ref)):
+        assert abs(per[t] - ref[t]) <= NORM_RTOL * ref[t], (t, per[t], ref[t])
+    assert per[18] == 0.0 and per[19] == 20.0
+    assert abs(per.sum() - omega.item()) <= 1e-12 * omega.item()
+    # a stage of empty tensors only, and a stage with no tensors
+    o, p = cf.cf_stage_grad_sqnorm_per_tensor(ctx, cf.Stage(ctx, [torch.empty(0, device=dev)] * 3))
+    assert o.item() == 0.0 and p.cpu().tolist() == [0.0, 0.0, 0.0]
+    o, p = cf.cf_stage_grad_sqnorm_per_tensor(ctx, cf.Stage(ctx, []))
+    assert o.item() == 0.0 and p.numel() == 0
+
+
 def test_sqnorm_bf16_gradients(ctx, dev):
     gen = torch.Generator(device=dev).manual_seed(17)
     shapes = workloads.ragged_shapes(8) + [(300_001,)]

@@ -133,3 +133,17 @@ def test_bf16_gradients_closed_form_and_exact_rational():
     # mixed stage: fp32 and bf16 tensors add up
     f = np.array([3.0, 4.0], np.float32)
     assert oracle.stage_grad_sqnorm([f, c]) == 25.0 + 1000 * 2.0 ** -14
+
+
+def test_per_tensor_norms_add_up_to_omega():
+    rng = np.random.default_rng(21)
+    tensors = [rng.normal(0, s, n).astype(np.float32) for s, n in [(1e-2, 1001), (1e-5, 17), (3e-4, 4096), (1.0, 0)]]
+    per = oracle.tensor_grad_sqnorms(tensors)
+    assert per[3] == 0.0
+    for t, g in zip(per, tensors):
+        exact = sum(Fraction(float(v)) ** 2 for v in g)
+        assert abs(Fraction(t) - exact) <= exact * Fraction(1, 10 ** 12)      # n * 2^-53 bound of plain summation
+    total = 0.0
+    for t in per:
+        total += t
+    assert total == oracle.stage_grad_sqnorm(tensors)          # same association: exact
