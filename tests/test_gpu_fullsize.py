@@ -73,3 +73,28 @@ def test_pipeline_norm_tracking_then_recovery(ctx, dev):
     want = oracle.recover_stage_weighted_avg(np_stage(wl.weights[lost - 1]), np_stage(wl.weights[lost + 1]),
                                              float(w[lost - 1]), float(w[lost + 1]), ORACLE_THREADS)
     assert_blend_close(np_stage(wl.weights[lost]), want)
+
+
+def test_one_tensor_beyond_four_gib(ctx, dev):
+    """Maximum-size case: a single tensor of 2^30 + 12345 fp32 elements (4.3 GB), so that element
+    offsets pass 2^30 and byte offsets pass 2^32 inside one tensor; 4.2 million blend tiles."""
+    n = (1 << 30) + 12345
+    print(f"huge tensor: {n} elements", flush=True)
+    const = torch.full((n,), 2.0 ** -7, device=dev)
+    omega = cf.cf_stage_grad_sqnorm(ctx, [cf.Stage(ctx, [const])])
+    assert omega.item() == n * 2.0 ** -14                      # every partial sum is exact
+    del const
+    gen = torch.Generator(device=dev).manual_seed(77)
+    a = torch.empty(n, device=dev).normal_(0, 0.02, generator=gen)
+    b = torch.empty(n, device=dev).normal_(0, 0.02, generator=gen)
+    a_host, b_host = workloads.to_numpy(a), workloads.to_numpy(b)
+    w = torch.tensor([3.7e-3, 1.9e-2], dtype=torch.float64, device=dev)
+    sa = cf.Stage(ctx, [a])
+    cf.cf_recover_stage_weighted_avg(ctx, sa, cf.Stage(ctx, [b]), w[0:1], w[1:2], sa)      # in place
+    torch.cuda.synchronize()
+    want = oracle.recover_stage_weighted_avg([a_host], [b_host], 3.7e-3, 1.9e-2, ORACLE_THREADS)
+    assert_blend_close([workloads.to_numpy(a)], want)
+    del want, a_host
+    cf.cf_copy_stage(ctx, cf.Stage(ctx, [b]), sa)
+    torch.cuda.synchronize()
+    assert torch.equal(a.view(torch.int32), b.view(torch.int32))

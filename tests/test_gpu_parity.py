@@ -44,14 +44,16 @@ def np_stage(stage):
     return workloads.stage_to_numpy(stage)
 
 
-def assert_blend_close(got_stage, want_stage):
+def assert_blend_close(got_stage, want_stage, piece=1 << 25):
     worst = 0
     for t, (g, w) in enumerate(zip(got_stage, want_stage)):
-        d = em.ulp_distance(g.reshape(-1), w.reshape(-1))
+        g, w = g.reshape(-1), w.reshape(-1)
         bar = F32_ULP if g.dtype == np.float32 else BF16_ULP
-        m = int(d.max()) if d.size else 0
-        assert m <= bar, f"tensor {t}: {m} ulp (bar {bar}), {int((d > bar).sum())} elements off"
-        worst = max(worst, m)
+        for lo in range(0, g.size, piece):                     # in pieces: the distance needs int64 temporaries
+            d = em.ulp_distance(g[lo:lo + piece], w[lo:lo + piece])
+            m = int(d.max())
+            assert m <= bar, f"tensor {t}: {m} ulp (bar {bar}), {int((d > bar).sum())} elements off from {lo}"
+            worst = max(worst, m)
     return worst
 
 
