@@ -38,6 +38,8 @@
  *     context's flag word (updated atomically) and, per stage handle, the
  *     scratch of cf_stage_grad_sqnorm: the same gradient-stage handle must not be
  *     in two cf_stage_grad_sqnorm calls that may run at the same time.
+ *   - Entry points may be called from several host threads; a handle must not be
+ *     destroyed while another thread still uses it.
  *   - Data-dependent conditions cannot be returned synchronously; they raise
  *     sticky bits in a device flag word read by cf_read_flags.
  */
@@ -113,7 +115,8 @@ typedef struct cf_stage cf_stage;  /* opaque: a stage's tensor list, uploaded on
 CF_API cf_status cf_ctx_create(int device, const cf_tuning *tuning, cf_ctx **out);
 
 /* Frees the context's device words.  Stages created from it must be destroyed
- * first.  NULL is accepted. */
+ * first: while any is alive this returns CF_ERR_CONTEXT and frees nothing.
+ * NULL is accepted. */
 CF_API cf_status cf_ctx_destroy(cf_ctx *ctx);
 
 /* Describes a stage: `tensors` is a HOST array of `num_tensors` descriptors,

@@ -19,6 +19,7 @@ equation, Algorithm 1) and "CheckFree+: First and Last Stage Recovery".
 """
 import ctypes
 import os
+import weakref
 
 _PKG = os.path.dirname(os.path.abspath(__file__))
 LIB_PATH = os.path.join(_PKG, "libcheckfree.so")
@@ -175,6 +176,7 @@ class Context:
         self.device = torch.device("cuda", device) if isinstance(device, int) else torch.device(device)
         index = self.device.index if self.device.index is not None else torch.cuda.current_device()
         self.device = torch.device("cuda", index)
+        self._stages = weakref.WeakSet()
         t = CfTuning(**{k: int(v) for k, v in tuning.items()}) if tuning else None
         lib = load_library()
         _check(lib.cf_ctx_create(index, ctypes.byref(t) if t is not None else None, ctypes.byref(self._h)),
@@ -187,7 +189,10 @@ class Context:
         return int(out.value)
 
     def close(self):
+        """Destroys the context and, first, every stage still alive on it."""
         if self._h:
+            for st in list(self._stages):
+                st.close()
             load_library().cf_ctx_destroy(self._h)
             self._h = ctypes.c_void_p()
 
@@ -212,6 +217,7 @@ class Stage:
         desc = tensor_descriptors(self.tensors)
         _check(load_library().cf_stage_create(ctx._h, desc, len(self.tensors), ctypes.byref(self._h)),
                "cf_stage_create")
+        ctx._stages.add(self)
 
     @property
     def numel(self):

@@ -6,6 +6,7 @@
 #include <algorithm>
 #include <atomic>
 #include <cstring>
+#include <mutex>
 #include <new>
 #include <vector>
 
@@ -40,7 +41,9 @@ struct cf_ctx {
     cf_tuning tuning{};
     uint32_t tile_shift = 0;   // log2(chunk_bytes / CF_TILE_BYTES)
     uint32_t *d_words = nullptr;
+    std::atomic<uint32_t> live_stages{0};
     // Pairs (input stage id, output stage id) whose congruence and aliasing have been checked.
+    std::mutex checked_mutex;
     std::vector<std::pair<uint64_t, uint64_t>> checked;
 };
 
@@ -158,6 +161,7 @@ cf_status check_self(const std::vector<HostTensor> &out)
 cf_status checked_pair(cf_ctx *ctx, const cf_stage *in, const cf_stage *out)
 {
     const std::pair<uint64_t, uint64_t> key(in->id, out->id);
+    std::lock_guard<std::mutex> lock(ctx->checked_mutex);
     if (std::find(ctx->checked.begin(), ctx->checked.end(), key) != ctx->checked.end()) return CF_OK;
     try {
         cf_status st = check_pair(in->tensors, out->tensors);
@@ -174,6 +178,7 @@ cf_status checked_pair(cf_ctx *ctx, const cf_stage *in, const cf_stage *out)
 
 void forget_stage(cf_ctx *ctx, uint64_t id)
 {
+    std::lock_guard<std::mutex> lock(ctx->checked_mutex);
     auto &v = ctx->checked;
     v.erase(std::remove_if(v.begin(), v.end(),
                            [id](const std::pair<uint64_t, uint64_t> &p) { return p.first == id || p.second == id; }),
@@ -314,6 +319,7 @@ cf_status cf_ctx_create(int device, const cf_tuning *tuning, cf_ctx **out)
 cf_status cf_ctx_destroy(cf_ctx *ctx)
 {
     if (!ctx) return CF_OK;
+    if (ctx->live_stages.load() != 0) return CF_ERR_CONTEXT;   // its stages still point at it: nothing is freed
     cf_status st = CF_OK;
     {
         DeviceGuard guard(ctx->device);
@@ -390,6 +396,7 @@ cf_status cf_stage_create(cf_ctx *ctx, const cf_tensor *tensors, uint32_t num_te
         stage->d_partials = static_cast<float *>(q);
         stage->d_tensor_first = static_cast<uint32_t *>(r);
     }
+    ctx->live_stages.fetch_add(1);
     *out = stage;
     return CF_OK;
 }
@@ -398,7 +405,8 @@ cf_status cf_stage_destroy(cf_stage *stage)
 {
     if (!stage) return CF_OK;
     cf_status st = CF_OK;
-    if (stage->ctx) forget_stage(stage->ctx, stage->id);
+    forget_stage(stage->ctx, stage->id);
+    stage->ctx->live_stages.fetch_sub(1);
     if (stage->d_chunks || stage->d_partials) {
         DeviceGuard guard(stage->ctx->device);
         if (!guard.ok()) st = CF_ERR_HIP;

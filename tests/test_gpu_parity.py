@@ -404,6 +404,19 @@ def test_copy_bit_exact_with_guard_bands(ctx, dev):
         assert (DH[:do] == 0).all() and (DH[do + 4099 - so:] == 0).all()
 
 
+def test_handle_lifetimes(dev):
+    lib = cf.load_library()
+    c = cf.Context(0)
+    st = cf.Stage(c, [torch.ones(10, device=dev)])
+    assert lib.cf_ctx_destroy(c._h) == cf.CF_ERR_CONTEXT          # a stage is still alive: nothing freed
+    omega = cf.cf_stage_grad_sqnorm(c, [st])                      # ... and everything still works
+    assert omega.item() == 10.0
+    c.close()                                                     # closes its stages first
+    assert not st._h and not c._h
+    st.close()                                                    # idempotent
+    c.close()
+
+
 def test_copy_argument_errors(ctx, dev):
     a = torch.zeros(300, device=dev)
     with pytest.raises(cf.CheckFreeError) as e:
