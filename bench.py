@@ -204,10 +204,48 @@ def main():
         },
     }
 
+    result["ceilings"] = measure_ceilings(args, wl, ctx, cf, torch, stream)
     if not args.no_cpu_baseline:
         result["cpu_baseline"] = cpu_baseline(args, wl, step_bytes, torch, workloads)
     print(json.dumps(result), flush=True)
     return 0
+
+
+def measure_ceilings(args, wl, ctx, cf, torch, stream, reps=20):
+    """What this machine sustains on one stage's worth of data (outside the timed region): a read-only
+    stream (the norm's first and second pass), this library's copy, and PyTorch's device-to-device
+    copy of the same tensors (the runtime's own copy kernel) as an outside reference."""
+    src_t = wl.weights[0] + wl.extra if args.config == 4 else wl.weights[wl.lost - 1]
+    dst_t = [torch.empty_like(t) for t in src_t]
+    src, dst = cf.Stage(ctx, src_t), cf.Stage(ctx, dst_t)
+    nbytes = src.nbytes
+    omega = torch.zeros(1, dtype=torch.float64, device=src_t[0].device)
+    readable = all(t.dtype in (torch.float32, torch.bfloat16) for t in src_t)
+
+    def timed(fn):
+        for _ in range(3):
+            fn()
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        e0.record(stream)
+        for _ in range(reps):
+            fn()
+        e1.record(stream)
+        e1.synchronize()
+        return e0.elapsed_time(e1) / reps
+
+    out = {"bytes_per_stream": int(nbytes)}
+    if readable:
+        ms = timed(lambda: cf.cf_stage_grad_sqnorm(ctx, [src], omega, stream))
+        out["read_only_GBps"] = round(nbytes / ms / 1e6, 1)
+    ms = timed(lambda: cf.cf_copy_stage(ctx, src, dst, stream))
+    out["copy_GBps"] = round(2 * nbytes / ms / 1e6, 1)
+    ms = timed(lambda: torch._foreach_copy_(dst_t, src_t))
+    out["torch_foreach_copy_GBps"] = round(2 * nbytes / ms / 1e6, 1)
+    flat_s = torch.empty(nbytes // 4, dtype=torch.float32, device=src_t[0].device).normal_()
+    flat_d = torch.empty_like(flat_s)
+    ms = timed(lambda: flat_d.copy_(flat_s))
+    out["torch_flat_copy_GBps"] = round(2 * flat_s.numel() * 4 / ms / 1e6, 1)
+    return out
 
 
 def cpu_baseline(args, wl, step_bytes, torch, workloads):

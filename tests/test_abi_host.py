@@ -204,3 +204,11 @@ def test_stage_pair_check_against_brute_force(lib):
                     bad = True
         want = cf.CF_ERR_ALIAS if bad else cf.CF_OK
         assert cf.check_stage_pair(ins, outs) == want, (ins, outs)
+
+
+def test_bench_refuses_more_than_one_gpu():
+    import subprocess
+    import sys
+    r = subprocess.run([sys.executable, os.path.join(ROOT, "bench.py"), "--gpus", "2"], capture_output=True, text=True)
+    assert r.returncode != 0
+    assert "one GPU" in r.stderr and r.stdout.strip() == ""

@@ -404,6 +404,55 @@ def test_copy_bit_exact_with_guard_bands(ctx, dev):
         assert (DH[:do] == 0).all() and (DH[do + 4099 - so:] == 0).all()
 
 
+def test_hot_calls_can_be_captured_in_a_hip_graph(dev):
+    """Callers under graph capture: the three hot calls enqueue kernels only (no
+    allocation, no copy, no synchronisation), so a captured recovery replays
+    correctly on changed inputs.  Replays alternate with eager work and are each
+    compared with the eager result bit for bit."""
+    c = cf.Context(0)
+    wl = workloads.make_workload(1, device=dev, shape=workloads.StageShape(192, 512, 2))
+    gp, gn = cf.Stage(c, wl.grads[0]), cf.Stage(c, wl.grads[2])
+    prev, nxt = cf.Stage(c, wl.weights[0]), cf.Stage(c, wl.weights[2])
+    out_g = [torch.zeros_like(t) for t in wl.weights[1]]
+    out_e = [torch.zeros_like(t) for t in wl.weights[1]]
+    cp_g = [torch.zeros_like(t) for t in wl.weights[1]]
+    lost_g, lost_e, copy_g = cf.Stage(c, out_g), cf.Stage(c, out_e), cf.Stage(c, cp_g)
+    om_g = torch.zeros(2, dtype=torch.float64, device=dev)
+    om_e = torch.zeros(2, dtype=torch.float64, device=dev)
+
+    def recovery(omega, lost, stream):
+        cf.cf_stage_grad_sqnorm(c, [gp, gn], omega, stream)
+        cf.cf_recover_stage_weighted_avg(c, prev, nxt, omega[0:1], omega[1:2], lost, stream)
+
+    side = torch.cuda.Stream()
+    graph = torch.cuda.CUDAGraph()
+    with torch.cuda.stream(side):
+        recovery(om_g, lost_g, side)                       # warm-up outside the capture
+        side.synchronize()
+        graph.capture_begin()
+        recovery(om_g, lost_g, side)
+        cf.cf_copy_stage(c, lost_g, copy_g, side)
+        graph.capture_end()
+    torch.cuda.synchronize()
+    for rep in range(4):
+        for g in wl.grads[0]:                              # new gradients => new omegas => new blend
+            g.mul_(1.5 + rep)
+        wl.weights[0][0].add_(0.001 * (rep + 1))
+        torch.cuda.synchronize()
+        recovery(om_e, lost_e, torch.cuda.current_stream())
+        torch.cuda.synchronize()
+        for t in out_g + cp_g:
+            t.zero_()
+        torch.cuda.synchronize()
+        graph.replay()
+        torch.cuda.synchronize()
+        assert om_g.cpu().numpy().tobytes() == om_e.cpu().numpy().tobytes(), rep
+        for x, y, z in zip(out_g, out_e, cp_g):
+            assert torch.equal(x.view(torch.int32), y.view(torch.int32)), rep
+            assert torch.equal(z.view(torch.int32), y.view(torch.int32)), rep
+    assert c.read_flags() == 0
+
+
 def test_handle_lifetimes(dev):
     lib = cf.load_library()
     c = cf.Context(0)
