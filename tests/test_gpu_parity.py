@@ -453,6 +453,55 @@ def test_hot_calls_can_be_captured_in_a_hip_graph(dev):
     assert c.read_flags() == 0
 
 
+@pytest.mark.parametrize("seed", range(12))
+def test_random_stages_all_operations(dev, seed):
+    """Seeded random stages: mixed fp32 / bf16 tensors, sizes from 0 to a few
+    chunks, random element offsets into their allocations (so the three streams
+    of a blend are sometimes mutually misaligned), random chunk size."""
+    rng = np.random.default_rng(1000 + seed)
+    gen = torch.Generator(device=dev).manual_seed(2000 + seed)
+    chunk_bytes = int(rng.choice([4096, 16384, 131072]))
+    c = cf.Context(0, chunk_bytes=chunk_bytes)
+    n_tensors = int(rng.integers(1, 9))
+    prev, nxt, out, grads, guards = [], [], [], [], []
+    for _ in range(n_tensors):
+        kind = rng.random()
+        n = 0 if kind < 0.1 else int(rng.integers(1, 40)) if kind < 0.3 else int(rng.integers(1, 5 * chunk_bytes // 4))
+        dtype = torch.bfloat16 if rng.random() < 0.4 else torch.float32
+        same_offsets = rng.random() < 0.6
+        offs = [int(rng.integers(0, 9))] * 3 if same_offsets else [int(x) for x in rng.integers(0, 9, 3)]
+        bufs = []
+        for k in range(3):
+            base = torch.empty(n + 16, device=dev).normal_(0, 0.02, generator=gen).to(dtype)
+            bufs.append(base)
+        out_base = torch.full((n + 16,), float("nan"), device=dev).to(dtype)
+        prev.append(bufs[0][offs[0]:offs[0] + n])
+        nxt.append(bufs[1][offs[1]:offs[1] + n])
+        out.append(out_base[offs[2]:offs[2] + n])
+        guards.append((out_base, offs[2], n))
+        g = torch.empty(n + 8, device=dev).normal_(0, float(10.0 ** rng.uniform(-5, -2)), generator=gen)
+        grads.append(g[offs[0] % 8:offs[0] % 8 + n] if rng.random() < 0.8 else g[:n].to(torch.bfloat16))
+    wp, wn = (10.0 ** rng.uniform(-8, 2, 2)).tolist()
+    sp, sn, so, sg = cf.Stage(c, prev), cf.Stage(c, nxt), cf.Stage(c, out), cf.Stage(c, grads)
+    omega, per = cf.cf_stage_grad_sqnorm_per_tensor(c, sg)
+    cf.cf_recover_stage_with_weights(c, sp, sn, wp, wn, so)
+    torch.cuda.synchronize()
+    ref = oracle.stage_grad_sqnorm(np_stage(grads))
+    assert abs(omega.item() - ref) <= NORM_RTOL * ref
+    for got, want in zip(per.cpu().numpy(), oracle.tensor_grad_sqnorms(np_stage(grads))):
+        assert abs(got - want) <= NORM_RTOL * want
+    assert_blend_close(np_stage(out), oracle.recover_stage_weighted_avg(np_stage(prev), np_stage(nxt), wp, wn))
+    for base, off, n in guards:                               # nothing written outside the tensors
+        assert torch.isnan(base[:off].float()).all() and torch.isnan(base[off + n:].float()).all()
+    cf.cf_copy_stage(c, sp, so)
+    torch.cuda.synchronize()
+    for g, w in zip(np_stage(out), oracle.copy_stage(np_stage(prev))):
+        assert g.tobytes() == w.tobytes()
+    for base, off, n in guards:
+        assert torch.isnan(base[:off].float()).all() and torch.isnan(base[off + n:].float()).all()
+    assert c.read_flags() == 0
+
+
 def test_handle_lifetimes(dev):
     lib = cf.load_library()
     c = cf.Context(0)
