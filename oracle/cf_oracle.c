@@ -53,7 +53,9 @@
 /* omega: squared L2 norm, binary64 accumulation, index order          */
 /* ------------------------------------------------------------------ */
 
-/* Sum of squares of one fp32 tensor, elements taken in index order. */
+/* Sum of squares of one fp32 tensor, elements taken in index order: one
+ * tensor's share of omega = ||grad W^S||^2 (section "CheckFree: Memoryless
+ * Recovery", definition of omega_{i-1}, omega_{i+1}). */
 double cfo_sqnorm_f32(const float *g, uint64_t n)
 {
     double acc = 0.0;
@@ -66,7 +68,8 @@ double cfo_sqnorm_f32(const float *g, uint64_t n)
 
 static double bf16_to_f64(uint16_t h);
 
-/* Sum of squares of one bfloat16 tensor (bit patterns), elements in index order. */
+/* The same share of omega for a bfloat16 gradient tensor (bit patterns),
+ * elements in index order. */
 double cfo_sqnorm_bf16(const uint16_t *g, uint64_t n)
 {
     double acc = 0.0;
@@ -77,7 +80,11 @@ double cfo_sqnorm_bf16(const uint16_t *g, uint64_t n)
     return acc;
 }
 
-/* omega of a stage: the tensors' sums of squares added in list order. */
+/* omega of a stage: the squared norm of ALL its gradient elements, i.e. the
+ * tensors' sums of squares added in list order (section "Problem Statement":
+ * a stage's weights are the combination of its layers' weights; section
+ * "CheckFree: Memoryless Recovery": omega is the squared gradient norm of
+ * the stage). */
 double cfo_stage_sqnorm_f32(const float *const *tensors, const uint64_t *numel,
                             uint32_t num_tensors)
 {
@@ -133,7 +140,9 @@ int cfo_effective_omega(double omega_prev, double omega_next, double *eff_prev, 
     return 1;
 }
 
-/* The display equation for one element, in binary64, written as printed. */
+/* The display equation of section "CheckFree: Memoryless Recovery" for one
+ * element, in binary64, written as printed: weighted sum of the two
+ * neighbours' values over the sum of the weights. */
 static double blend_value(double wp, double wn, double a, double b)
 {
     double numerator = wp * a + wn * b;
@@ -184,6 +193,9 @@ uint16_t cfo_f64_to_bf16(double x) { return f64_to_bf16(x); }
 /* blend: one tensor                                                    */
 /* ------------------------------------------------------------------ */
 
+/* W^S_i for one fp32 tensor pair: the display equation element by element,
+ * rounded once to binary32 (Algorithm 1, third step, with the display
+ * equation's weights). */
 void cfo_blend_f32(double omega_prev, double omega_next, const float *prev, const float *next,
                    float *out, uint64_t n, int threads)
 {
@@ -195,6 +207,7 @@ void cfo_blend_f32(double omega_prev, double omega_next, const float *prev, cons
         out[k] = (float)blend_value(wp, wn, (double)prev[k], (double)next[k]);
 }
 
+/* The same for a bfloat16 tensor pair, rounded once to bfloat16. */
 void cfo_blend_bf16(double omega_prev, double omega_next, const uint16_t *prev,
                     const uint16_t *next, uint16_t *out, uint64_t n, int threads)
 {
@@ -220,6 +233,9 @@ void cfo_blend_f64(double omega_prev, double omega_next, const double *prev, con
 /* copy                                                                 */
 /* ------------------------------------------------------------------ */
 
+/* CheckFree+ (section "CheckFree+: First and Last Stage Recovery"): an end
+ * stage from its neighbour, embedding and de-embedding from their replicas,
+ * "exactly": the bytes of src, unchanged. */
 void cfo_copy_bytes(void *dst, const void *src, uint64_t nbytes, int threads)
 {
     if (threads <= 1) {
