@@ -43,6 +43,24 @@ def build(verbose=True):
     return LIB
 
 
+C_SMOKE_SRC = os.path.join(ROOT, "tests", "c_abi_smoke.c")
+C_SMOKE_BIN = os.path.join(ROOT, "tests", "c_abi_smoke")
+
+
+def build_c_smoke(verbose=True):
+    """The plain-C99 client of the ABI used by the tests (gcc, no HIP compiler)."""
+    rocm = os.environ.get("ROCM_PATH", "/opt/rocm")
+    cmd = ["gcc", "-std=c99", "-Wall", "-Wextra", "-Werror", "-pedantic", "-O1", "-D__HIP_PLATFORM_AMD__",
+           "-I", os.path.join(ROOT, "include"), "-isystem", os.path.join(rocm, "include"), C_SMOKE_SRC,
+           "-o", C_SMOKE_BIN, "-L", PKG, "-lcheckfree", "-L", os.path.join(rocm, "lib"), "-lamdhip64", "-lm",
+           "-Wl,-rpath,$ORIGIN/../paper_2506_15461_amd", "-Wl,-rpath," + os.path.join(rocm, "lib")]
+    if verbose:
+        print(" ".join(cmd), flush=True)
+    subprocess.run(cmd, check=True)
+    return C_SMOKE_BIN
+
+
 if __name__ == "__main__":
     build()
+    build_c_smoke()
     sys.exit(0)

@@ -212,3 +212,15 @@ def test_bench_refuses_more_than_one_gpu():
     r = subprocess.run([sys.executable, os.path.join(ROOT, "bench.py"), "--gpus", "2"], capture_output=True, text=True)
     assert r.returncode != 0
     assert "one GPU" in r.stderr and r.stdout.strip() == ""
+
+
+def test_plain_c_client_host_only(lib):
+    """A C99 program (gcc -pedantic -Werror) includes the header, links the library and calls the
+    host-only entry points."""
+    import subprocess
+    from paper_2506_15461_amd import build as hip_build
+    if not os.path.exists(hip_build.C_SMOKE_BIN):
+        hip_build.build_c_smoke(verbose=False)
+    r = subprocess.run([hip_build.C_SMOKE_BIN, "--host-only"], capture_output=True, text=True)
+    assert r.returncode == 0, r.stderr
+    assert "host-only ok" in r.stdout

@@ -502,6 +502,18 @@ def test_random_stages_all_operations(dev, seed):
     assert c.read_flags() == 0
 
 
+def test_plain_c_client_on_the_device():
+    """The C99 client drives the whole path through the C ABI with hipMalloc'd
+    buffers: no PyTorch, no C++ on the caller's side."""
+    import os
+    import subprocess
+    from paper_2506_15461_amd import build as hip_build
+    assert os.path.exists(hip_build.C_SMOKE_BIN), "run __graft_entry__.build() first"
+    r = subprocess.run([hip_build.C_SMOKE_BIN], capture_output=True, text=True, timeout=120)
+    assert r.returncode == 0, r.stdout + r.stderr
+    assert "c_abi_smoke: ok" in r.stdout
+
+
 def test_handle_lifetimes(dev):
     lib = cf.load_library()
     c = cf.Context(0)
