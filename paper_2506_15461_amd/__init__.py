@@ -196,6 +196,12 @@ class Context:
             load_library().cf_ctx_destroy(self._h)
             self._h = ctypes.c_void_p()
 
+    def __enter__(self):
+        return self
+
+    def __exit__(self, *exc):
+        self.close()
+
     def __del__(self):
         try:
             self.close()
@@ -218,6 +224,9 @@ class Stage:
         _check(load_library().cf_stage_create(ctx._h, desc, len(self.tensors), ctypes.byref(self._h)),
                "cf_stage_create")
         ctx._stages.add(self)
+
+    def __repr__(self):
+        return f"Stage({len(self.tensors)} tensors, {self.numel} elements, {self.nbytes} bytes, {self.num_chunks} chunks)"
 
     @property
     def numel(self):

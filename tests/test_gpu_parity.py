@@ -514,6 +514,36 @@ def test_plain_c_client_on_the_device():
     assert "c_abi_smoke: ok" in r.stdout
 
 
+def test_two_recoveries_on_two_streams_at_once(dev):
+    """Independent recoveries issued on two streams (default priority), one
+    context each, interleaved call by call."""
+    wls = [workloads.make_workload(1, device=dev, shape=workloads.StageShape(256, 704, 2), seed=900 + i) for i in (0, 1)]
+    streams = [torch.cuda.Stream(), torch.cuda.Stream()]
+    ctxs = [cf.Context(0), cf.Context(0)]
+    torch.cuda.synchronize()
+    handles, omegas = [], []
+    for wl, c in zip(wls, ctxs):
+        for t in wl.weights[1]:
+            t.fill_(float("nan"))
+        handles.append(dict(gp=cf.Stage(c, wl.grads[0]), gn=cf.Stage(c, wl.grads[2]), prev=cf.Stage(c, wl.weights[0]),
+                            nxt=cf.Stage(c, wl.weights[2]), lost=cf.Stage(c, wl.weights[1])))
+        omegas.append(torch.zeros(2, dtype=torch.float64, device=dev))
+    torch.cuda.synchronize()
+    for rep in range(5):
+        for h, c, om, st in zip(handles, ctxs, omegas, streams):
+            cf.cf_stage_grad_sqnorm(c, [h["gp"], h["gn"]], om, st)
+        for h, c, om, st in zip(handles, ctxs, omegas, streams):
+            cf.cf_recover_stage_weighted_avg(c, h["prev"], h["nxt"], om[0:1], om[1:2], h["lost"], st)
+    torch.cuda.synchronize()
+    for wl, om in zip(wls, omegas):
+        w = om.cpu().numpy()
+        for k, s in enumerate((0, 2)):
+            ref = oracle.stage_grad_sqnorm(np_stage(wl.grads[s]))
+            assert abs(w[k] - ref) <= NORM_RTOL * ref
+        want = oracle.recover_stage_weighted_avg(np_stage(wl.weights[0]), np_stage(wl.weights[2]), float(w[0]), float(w[1]))
+        assert_blend_close(np_stage(wl.weights[1]), want)
+
+
 def test_handle_lifetimes(dev):
     lib = cf.load_library()
     c = cf.Context(0)
