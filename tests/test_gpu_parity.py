@@ -67,7 +67,30 @@ def run_recovery(ctx, weights_prev, weights_next, weights_lost, grads_prev, grad
     return omega.cpu().numpy()
 
 
-def check_recovery(ctx, wl, prev_i, lost_i, next_i):
+def as_f64(a):
+    """Values of an fp32 array or of bf16 bit patterns, as float64."""
+    if a.dtype == np.uint16:
+        return (a.astype(np.uint32) << 16).view(np.float32).astype(np.float64)
+    return a.astype(np.float64)
+
+
+def assert_end_to_end_within_sensitivity_bound(got_stage, prev, nxt, omega_gpu, omega_ref):
+    """End to end (GPU omegas -> GPU blend against oracle omegas -> oracle blend) the result moves
+    with the omegas: out = b + alpha (a - b), alpha = w_p / (w_p + w_n), so to first order
+    |d out| <= alpha beta |a - b| (|d_p| + |d_n|), d_* the relative errors of the omegas; on top of
+    that each side rounds once to the storage type."""
+    wp, wn = omega_ref
+    alpha, beta = wp / (wp + wn), wn / (wp + wn)
+    dp, dn = abs(omega_gpu[0] - wp) / wp, abs(omega_gpu[1] - wn) / wn
+    want_stage = oracle.recover_stage_weighted_avg(prev, nxt, wp, wn, ORACLE_THREADS)
+    for g, w, a, b in zip(got_stage, want_stage, prev, nxt):
+        gv, wv, av, bv = (as_f64(x).reshape(-1) for x in (g, w, a, b))
+        ulp = np.spacing(np.abs(wv).astype(np.float32)).astype(np.float64) * (65536.0 if g.dtype == np.uint16 else 1.0)
+        bound = 1.01 * alpha * beta * np.abs(av - bv) * (dp + dn) + 2.0 * ulp
+        assert np.all(np.abs(gv - wv) <= bound)
+
+
+def check_recovery(ctx, wl, prev_i, lost_i, next_i, end_to_end=False):
     for t in wl.weights[lost_i]:
         t.fill_(float("nan"))                      # the lost stage's content is gone
     omega = run_recovery(ctx, wl.weights[prev_i], wl.weights[next_i], wl.weights[lost_i],
@@ -75,9 +98,16 @@ def check_recovery(ctx, wl, prev_i, lost_i, next_i):
     for k, s in enumerate((prev_i, next_i)):
         ref = oracle.stage_grad_sqnorm(np_stage(wl.grads[s]), ORACLE_THREADS)
         assert abs(omega[k] - ref) <= NORM_RTOL * ref, (s, omega[k], ref)
+    refs = []
+    for k, s in enumerate((prev_i, next_i)):
+        refs.append(oracle.stage_grad_sqnorm(np_stage(wl.grads[s]), ORACLE_THREADS))
     want = oracle.recover_stage_weighted_avg(np_stage(wl.weights[prev_i]), np_stage(wl.weights[next_i]),
                                              float(omega[0]), float(omega[1]), ORACLE_THREADS)
-    return omega, assert_blend_close(np_stage(wl.weights[lost_i]), want)
+    worst = assert_blend_close(np_stage(wl.weights[lost_i]), want)
+    if end_to_end:
+        assert_end_to_end_within_sensitivity_bound(np_stage(wl.weights[lost_i]), np_stage(wl.weights[prev_i]),
+                                                   np_stage(wl.weights[next_i]), omega, refs)
+    return omega, worst
 
 
 # ----------------------------------------------------------------------------
@@ -580,4 +610,4 @@ def test_copy_argument_errors(ctx, dev):
 ])
 def test_recovery_reduced_shapes(ctx, dev, config, shape):
     wl = workloads.make_workload(config, device=dev, shape=shape)
-    check_recovery(ctx, wl, 0, 1, 2)
+    check_recovery(ctx, wl, 0, 1, 2, end_to_end=True)
