@@ -294,9 +294,29 @@ def cpu_baseline(args, wl, step_bytes, torch, workloads):
         if el * threads >= args.cpu_seconds or reps >= 50:
             break
     sec = el / reps
-    return {"value": round(nbytes / sec / 1e9, 2), "unit": "GB/s", "cores": threads, "kind": "oracle",
-            "ms_per_step": round(sec * 1e3, 2),
-            "sample": f"{sample}; {reps} repetition(s), {el:.1f} s wall on {threads} thread(s)"}
+    out = {"value": round(nbytes / sec / 1e9, 2), "unit": "GB/s", "cores": threads, "kind": "oracle",
+           "ms_per_step": round(sec * 1e3, 2),
+           "sample": f"{sample}; {reps} repetition(s), {el:.1f} s wall on {threads} thread(s)"}
+    if threads > 1:
+        # the same step once on a single thread, for scale
+        threads = 1
+        t0 = time.perf_counter()
+        cpu_step()
+        sec1 = time.perf_counter() - t0
+        out["single_thread"] = {"value": round(nbytes / sec1 / 1e9, 2), "unit": "GB/s", "ms_per_step": round(sec1 * 1e3, 1)}
+    out["host"] = {"cpu_model": cpu_model(), "logical_cpus": os.cpu_count()}
+    return out
+
+
+def cpu_model():
+    try:
+        with open("/proc/cpuinfo") as f:
+            for line in f:
+                if line.startswith("model name"):
+                    return line.split(":", 1)[1].strip()
+    except OSError:
+        pass
+    return "unknown"
 
 
 if __name__ == "__main__":
