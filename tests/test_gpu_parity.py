@@ -574,6 +574,26 @@ def test_two_recoveries_on_two_streams_at_once(dev):
         assert_blend_close(np_stage(wl.weights[1]), want)
 
 
+def test_empty_stages_and_empty_calls(ctx, dev):
+    empty = cf.Stage(ctx, [])
+    hollow = cf.Stage(ctx, [torch.empty(0, device=dev), torch.empty(0, device=dev, dtype=torch.bfloat16)])
+    hollow2 = cf.Stage(ctx, [torch.empty(0, device=dev), torch.empty(0, device=dev, dtype=torch.bfloat16)])
+    w = _omega(dev, 1.0, 2.0)
+    cf.cf_recover_stage_weighted_avg(ctx, empty, empty, w[0:1], w[1:2], cf.Stage(ctx, []))      # nothing to do
+    cf.cf_recover_stage_with_weights(ctx, hollow, hollow2, 1.0, 1.0, cf.Stage(ctx, [torch.empty(0, device=dev), torch.empty(0, device=dev, dtype=torch.bfloat16)]))
+    cf.cf_copy_stage(ctx, hollow, hollow2)
+    cf.cf_copy_stage(ctx, empty, cf.Stage(ctx, []))
+    out = cf.cf_stage_grad_sqnorm(ctx, [])                           # no stages: no launch, empty result
+    assert out.numel() == 0
+    om = cf.cf_stage_grad_sqnorm(ctx, [empty, hollow]).cpu().numpy()
+    assert om.tolist() == [0.0, 0.0]
+    g = cf.Stage(ctx, [torch.full((70_000,), 0.5, device=dev)])
+    om = cf.cf_stage_grad_sqnorm(ctx, [g, empty, g]).cpu().numpy()   # a handle twice in one call
+    assert om.tolist() == [17500.0, 0.0, 17500.0]
+    torch.cuda.synchronize()
+    assert ctx.read_flags() == 0
+
+
 def test_handle_lifetimes(dev):
     lib = cf.load_library()
     c = cf.Context(0)
