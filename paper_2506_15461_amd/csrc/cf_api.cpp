@@ -431,6 +431,13 @@ cf_status cf_stage_grad_sqnorm(cf_ctx *ctx, const cf_stage *const *grad_stages, 
         if (!grad_stages[s]) return CF_ERR_NULL;
         if (grad_stages[s]->ctx != ctx) return CF_ERR_CONTEXT;
     }
+    // Every group of stages must fit one launch before anything is launched.
+    for (uint32_t base = 0; base < n_stages; base += CF_MAX_SEG) {
+        const uint32_t n = std::min<uint32_t>(CF_MAX_SEG, n_stages - base);
+        uint64_t total = 0;
+        for (uint32_t k = 0; k < n; ++k) total += grad_stages[base + k]->n_chunks;
+        if (total >= kMaxChunksPerStage) return CF_ERR_LIMIT;
+    }
     DeviceGuard guard(ctx->device);
     if (!guard.ok()) return CF_ERR_HIP;
     for (uint32_t base = 0; base < n_stages; base += CF_MAX_SEG) {
@@ -445,7 +452,6 @@ cf_status cf_stage_grad_sqnorm(cf_ctx *ctx, const cf_stage *const *grad_stages, 
             args.seg[k].chunk_begin = (uint32_t)total;
             args.seg[k].n_chunks = st->n_chunks;
             total += st->n_chunks;
-            if (total >= kMaxChunksPerStage) return CF_ERR_LIMIT;
         }
         args.n_seg = n;
         args.total_chunks = (uint32_t)total;
