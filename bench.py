@@ -57,7 +57,7 @@ def parse():
 def main():
     args = parse()
     if args.gpus != 1:
-        print(f"bench.py: this build runs on exactly one GPU (asked for {args.gpus}); "
+        print(f"bench.py: this library runs on exactly one GPU (asked for {args.gpus}); "
               "the path has no multi-GPU leg.", file=sys.stderr)
         return 2
 
