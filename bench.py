@@ -172,7 +172,8 @@ def main():
         traffic = TRAFFIC_BYTES_PER_LAUNCH.get((args.config, dominant_kernel))
 
     result = {
-        "metric": "stage_recovery_hbm_throughput",
+        "metric": "stage_recovery_achieved_hbm_bandwidth",
+        "stage_recovery_ms": round(ms_per_step, 5),
         "value": round(gbps, 1),
         "unit": "GB/s",
         "n_gpus": 1,
