@@ -162,6 +162,8 @@ def main():
     for j, name in enumerate(kernels):
         d = np.array([events[k][j].elapsed_time(events[k][j + 1]) for k in sampled])
         kernel_ms[name] = {"avg": float(d.mean()), "median": float(np.median(d)), "min": float(d.min())}
+    d = np.array([events[k][0].elapsed_time(events[k][-1]) for k in sampled])
+    sampled_step = {"median": round(float(np.median(d)), 5), "min": round(float(d.min()), 5), "n": len(sampled)}
     gbps = step_bytes / (ms_per_step * 1e-3) / 1e9
     dom_ms = kernel_ms[dominant]["avg"]
     achieved = kernel_bytes[dominant] / (dom_ms * 1e-3) / 1e9
@@ -174,6 +176,7 @@ def main():
     result = {
         "metric": "stage_recovery_achieved_hbm_bandwidth",
         "stage_recovery_ms": round(ms_per_step, 5),
+        "sampled_step_ms": sampled_step,
         "value": round(gbps, 1),
         "unit": "GB/s",
         "n_gpus": 1,
