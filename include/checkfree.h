@@ -170,8 +170,6 @@ CF_API cf_status cf_stage_grad_sqnorm(cf_ctx *ctx, const cf_stage *const *grad_s
  *
  * The per-tensor values are each a fixed-order binary64 sum of that tensor's
  * partials; their sum equals omega up to binary64 rounding, not bit for bit.
- * (If the stage holds only empty tensors the zeros are written with
- * hipMemsetAsync; do not capture that case into a HIP graph.)
  * Errors: CF_ERR_NULL, CF_ERR_CONTEXT, CF_ERR_LIMIT, CF_ERR_HIP. */
 CF_API cf_status cf_stage_grad_sqnorm_per_tensor(cf_ctx *ctx, const cf_stage *grad_stage,
                                                  double *d_tensor_sqnorm, double *d_omega_out, void *stream);

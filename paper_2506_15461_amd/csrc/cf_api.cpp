@@ -374,16 +374,19 @@ cf_status cf_stage_create(cf_ctx *ctx, const cf_tensor *tensors, uint32_t num_te
         }
     }
     tensor_first.push_back((uint32_t)table.size());
-    if (n_chunks) {
+    if (num_tensors) {
         DeviceGuard guard(ctx->device);
         void *p = nullptr, *q = nullptr, *r = nullptr;
-        bool ok = guard.ok() && hipMalloc(&p, n_chunks * sizeof(CfChunk)) == hipSuccess;
+        bool ok = guard.ok();
         ok = ok && hipMalloc(&r, tensor_first.size() * sizeof(uint32_t)) == hipSuccess;
         ok = ok && hipMemcpy(r, tensor_first.data(), tensor_first.size() * sizeof(uint32_t),
                              hipMemcpyHostToDevice) == hipSuccess;
-        ok = ok && hipMalloc(&q, n_chunks * sizeof(float)) == hipSuccess;
-        ok = ok && hipMemcpy(p, table.data(), n_chunks * sizeof(CfChunk), hipMemcpyHostToDevice) == hipSuccess;
-        ok = ok && hipMemset(q, 0, n_chunks * sizeof(float)) == hipSuccess;
+        if (n_chunks) {
+            ok = ok && hipMalloc(&p, n_chunks * sizeof(CfChunk)) == hipSuccess;
+            ok = ok && hipMalloc(&q, n_chunks * sizeof(float)) == hipSuccess;
+            ok = ok && hipMemcpy(p, table.data(), n_chunks * sizeof(CfChunk), hipMemcpyHostToDevice) == hipSuccess;
+            ok = ok && hipMemset(q, 0, n_chunks * sizeof(float)) == hipSuccess;
+        }
         ok = ok && hipDeviceSynchronize() == hipSuccess;
         if (!ok) {
             if (p) (void)hipFree(p);
@@ -407,7 +410,7 @@ cf_status cf_stage_destroy(cf_stage *stage)
     cf_status st = CF_OK;
     forget_stage(stage->ctx, stage->id);
     stage->ctx->live_stages.fetch_sub(1);
-    if (stage->d_chunks || stage->d_partials) {
+    if (stage->d_chunks || stage->d_partials || stage->d_tensor_first) {
         DeviceGuard guard(stage->ctx->device);
         if (!guard.ok()) st = CF_ERR_HIP;
         if (stage->d_chunks && hipFree(stage->d_chunks) != hipSuccess) st = CF_ERR_HIP;
@@ -474,13 +477,6 @@ cf_status cf_stage_grad_sqnorm_per_tensor(cf_ctx *ctx, const cf_stage *grad_stag
     if (grad_stage->tensors.empty()) return CF_OK;
     DeviceGuard guard(ctx->device);
     if (!guard.ok()) return CF_ERR_HIP;
-    if (grad_stage->n_chunks == 0) {
-        // only empty tensors: their norms are zero; no partials exist to add up
-        if (hipMemsetAsync(d_tensor_sqnorm, 0, grad_stage->tensors.size() * sizeof(double),
-                           static_cast<hipStream_t>(stream)) != hipSuccess)
-            return CF_ERR_HIP;
-        return CF_OK;
-    }
     if (cf_launch_sqnorm_tensors(grad_stage->d_partials, grad_stage->d_tensor_first,
                                  (uint32_t)grad_stage->tensors.size(), d_tensor_sqnorm,
                                  static_cast<hipStream_t>(stream)) != hipSuccess)
