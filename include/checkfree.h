@@ -123,9 +123,11 @@ CF_API cf_status cf_ctx_destroy(cf_ctx *ctx);
  * borrowed only for the duration of this call (its contents are copied).  The
  * tensors' memory is borrowed for as long as the stage handle is used; the
  * caller keeps it alive and at the same addresses.  num_tensors may be 0.
- * Uploads the stage's chunk table with one blocking host-to-device copy.
- * Errors: CF_ERR_NULL, CF_ERR_DTYPE, CF_ERR_ALIGN, CF_ERR_LIMIT (more than 2^31
- * chunks), CF_ERR_HIP. */
+ * Allocates the stage's device tables (20 bytes per chunk, 4 bytes per tensor)
+ * and uploads them with blocking host-to-device copies.
+ * Errors: CF_ERR_NULL, CF_ERR_DTYPE, CF_ERR_ALIGN, CF_ERR_LIMIT (a tensor above
+ * 2^40 elements, or a stage above 2^31 - 1 one-KiB tiles, about 2 TiB),
+ * CF_ERR_HIP. */
 CF_API cf_status cf_stage_create(cf_ctx *ctx, const cf_tensor *tensors, uint32_t num_tensors, cf_stage **out);
 
 /* Frees the stage's tables (never the tensors).  NULL is accepted. */
