@@ -168,6 +168,21 @@ def test_sqnorm_misaligned_views(ctx, dev):
     assert abs(omega[0] - ref) <= NORM_RTOL * ref
 
 
+def test_sqnorm_adversarial_rounding_stays_inside_the_bound(ctx, dev):
+    """Data built against fp32 accumulation: every accumulator chain starts with 1.0 and is then fed
+    31 squares of just under half an ulp of 1.0, all of which fp32 rounds away.  All terms of a sum of
+    squares are non-negative, so the relative error cannot exceed about (32 + 10) * 2^-24 = 2.5e-6."""
+    chunk = 32768                                        # elements per default chunk
+    n_chunks = 40
+    g = torch.full((n_chunks * chunk,), 2.0 ** -12.6, device=dev)
+    v = g.view(n_chunks, 32, 256, 4)                     # [chunk, iteration, lane, vector slot]
+    v[:, 0, :, :] = 1.0
+    omega = cf.cf_stage_grad_sqnorm(ctx, [cf.Stage(ctx, [g])]).item()
+    ref = oracle.stage_grad_sqnorm([workloads.to_numpy(g)])
+    rel = abs(omega - ref) / ref
+    assert 1e-7 < rel <= 2.5e-6, rel                     # the loss is real, and inside the bound
+
+
 def test_sqnorm_nonfinite_raises_flag(dev):
     c = cf.Context(0)
     g = torch.ones(5000, device=dev)
