@@ -212,6 +212,7 @@ def main():
             "unit": "GB/s",
             "frac": round(achieved / HBM_PEAK_GBPS, 4),
             "traffic": traffic,
+            "traffic_unit": "bytes per launch (rocprofv3 FETCH_SIZE + WRITE_SIZE, each scaled by the copy kernel's)",
             "algorithmic_bytes_per_launch": int(kernel_bytes[dominant]),
         },
     }
