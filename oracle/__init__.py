@@ -5,8 +5,8 @@ check and by the benchmark's CPU-baseline leg.  It imports nothing from the HIP
 package and the HIP package imports nothing from here.
 
 A *stage* is an ordered list of numpy arrays, one per weight (or gradient)
-tensor, exactly the paper's "combination of weights of the layers in that
-stage" (section "Problem Statement", paragraph "Distributed Training").
+tensor: a stage's weights are the weight tensors of its layers taken together
+(section "Problem Statement", paragraph "Distributed Training").
 dtype float32 is fp32; dtype uint16 holds bfloat16 bit patterns.
 
 Functions (paper: section "CheckFree: Memoryless Recovery", its display
@@ -17,6 +17,7 @@ equation and Algorithm 1; section "CheckFree+: First and Last Stage Recovery"):
   recover_stage_weighted_avg(prev, next, ..)  W^S_i = (w_{i-1} W_{i-1} + w_{i+1} W_{i+1}) / (w_{i-1} + w_{i+1})
   blend_unrounded(prev, next, ..)             the same value in binary64, not narrowed
   copy_stage(src)                             bytewise copy (CheckFree+)
+  copy_stage_ranges(src, dst, ranges)         slices of that copy (keeping a replica current piece by piece)
 """
 import ctypes
 import os
@@ -58,6 +59,11 @@ def _lib():
         lib.cfo_copy_bytes.restype = None
         lib.cfo_copy_bytes.argtypes = [ctypes.c_void_p, ctypes.c_void_p, ctypes.c_uint64,
                                        ctypes.c_int]
+        lib.cfo_copy_range.restype = None
+        lib.cfo_copy_range.argtypes = [ctypes.c_void_p, ctypes.c_void_p, ctypes.c_uint64, ctypes.c_uint64,
+                                       ctypes.c_uint32]
+        lib.cfo_common_scale.restype = None
+        lib.cfo_common_scale.argtypes = [c_dp, c_dp]
         lib.cfo_bf16_to_f64.restype = ctypes.c_double
         lib.cfo_bf16_to_f64.argtypes = [ctypes.c_uint16]
         lib.cfo_f64_to_bf16.restype = ctypes.c_uint16
@@ -117,6 +123,14 @@ def effective_omega(omega_prev: float, omega_next: float):
     return ep.value, en.value, bool(flag)
 
 
+def common_scale(omega_prev: float, omega_next: float):
+    """Both weights times the power of two that brings their sum into [1, 2): the
+    form in which the blend uses them (the equation is unchanged by a common factor)."""
+    wp, wn = ctypes.c_double(float(omega_prev)), ctypes.c_double(float(omega_next))
+    _lib().cfo_common_scale(ctypes.byref(wp), ctypes.byref(wn))
+    return wp.value, wn.value
+
+
 def recover_stage_weighted_avg(prev, next, omega_prev: float, omega_next: float,
                                threads: int = 1):
     """The lost stage: for every tensor pair of the two neighbouring stages the
@@ -163,6 +177,20 @@ def copy_stage(src, threads: int = 1):
         _lib().cfo_copy_bytes(d.ctypes.data, s.ctypes.data, s.nbytes, int(threads))
         out.append(d)
     return out
+
+
+def copy_stage_ranges(src, dst, ranges):
+    """Slices of a stage copy: for every (tensor index, first element, element
+    count) in `ranges` those elements of src's tensor are carried into dst's,
+    in place; everything else in dst is left alone.  Returns dst."""
+    for t, first, count in ranges:
+        s, d = src[t], dst[t]
+        if s.shape != d.shape or s.dtype != d.dtype or not (s.flags.c_contiguous and d.flags.c_contiguous):
+            raise ValueError("source and destination tensors are not congruent contiguous arrays")
+        if first < 0 or count < 0 or first + count > s.size:
+            raise ValueError("range outside the tensor")
+        _lib().cfo_copy_range(d.ctypes.data, s.ctypes.data, int(first), int(count), s.itemsize)
+    return dst
 
 
 def bf16_to_f64(bits: int) -> float:

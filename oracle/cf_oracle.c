@@ -21,14 +21,15 @@
  *                                        omega_{i-1} on both terms; the display
  *                                        equation is taken as authoritative,
  *                                        because only it is consistent with the
- *                                        section's own special cases
- *                                        "omega_{i+1} = 0 is a copy of the
- *                                        previous stage" and "equal omegas are
- *                                        the uniform average".)
+ *                                        section's own special cases: a zero
+ *                                        omega_{i+1} reduces it to a copy of
+ *                                        the previous stage, equal omegas to
+ *                                        the uniform average.)
  *
  *   copy     : CheckFree+ (section "CheckFree+: First and Last Stage
  *              Recovery") restores a first/last stage from its neighbour and
- *              the (de)embedding from a replica "exactly": a bytewise copy.
+ *              the (de)embedding from a replica without any loss: a bytewise
+ *              copy.
  *
  * Arithmetic: all floating point in IEEE binary64, evaluated literally in the
  * order the formulas are written (compile with -ffp-contract=off so that no
@@ -140,6 +141,23 @@ int cfo_effective_omega(double omega_prev, double omega_next, double *eff_prev, 
     return 1;
 }
 
+/* The display equation of section "CheckFree: Memoryless Recovery" is a ratio
+ * of two expressions linear in (omega_{i-1}, omega_{i+1}): multiplying both
+ * omegas by one positive number leaves W^S_i unchanged.  The blend uses that
+ * freedom once, before any element is touched: both weights are multiplied by
+ * the power of two that brings their binary64 sum into [1, 2).  A power of two
+ * changes no significand, so wherever the unscaled formula stays inside the
+ * binary64 range the scaled one gives the same bits; where it would not (omegas
+ * near 1e300 or 1e-300 against weights of ordinary size) the scaled one still
+ * gives the value of the equation. */
+void cfo_common_scale(double *wp, double *wn)
+{
+    int e;
+    (void)frexp(*wp + *wn, &e);       /* sum = m * 2^e, m in [0.5, 1) */
+    *wp = ldexp(*wp, 1 - e);
+    *wn = ldexp(*wn, 1 - e);
+}
+
 /* The display equation of section "CheckFree: Memoryless Recovery" for one
  * element, in binary64, written as printed: weighted sum of the two
  * neighbours' values over the sum of the weights. */
@@ -201,6 +219,7 @@ void cfo_blend_f32(double omega_prev, double omega_next, const float *prev, cons
 {
     double wp, wn;
     cfo_effective_omega(omega_prev, omega_next, &wp, &wn);
+    cfo_common_scale(&wp, &wn);
     if (threads < 1) threads = 1;
 #pragma omp parallel for num_threads(threads) schedule(static)
     for (uint64_t k = 0; k < n; ++k)
@@ -213,6 +232,7 @@ void cfo_blend_bf16(double omega_prev, double omega_next, const uint16_t *prev,
 {
     double wp, wn;
     cfo_effective_omega(omega_prev, omega_next, &wp, &wn);
+    cfo_common_scale(&wp, &wn);
     if (threads < 1) threads = 1;
 #pragma omp parallel for num_threads(threads) schedule(static)
     for (uint64_t k = 0; k < n; ++k)
@@ -226,6 +246,7 @@ void cfo_blend_f64(double omega_prev, double omega_next, const double *prev, con
 {
     double wp, wn;
     cfo_effective_omega(omega_prev, omega_next, &wp, &wn);
+    cfo_common_scale(&wp, &wn);
     for (uint64_t k = 0; k < n; ++k) out[k] = blend_value(wp, wn, prev[k], next[k]);
 }
 
@@ -235,7 +256,7 @@ void cfo_blend_f64(double omega_prev, double omega_next, const double *prev, con
 
 /* CheckFree+ (section "CheckFree+: First and Last Stage Recovery"): an end
  * stage from its neighbour, embedding and de-embedding from their replicas,
- * "exactly": the bytes of src, unchanged. */
+ * without loss: the bytes of src, unchanged. */
 void cfo_copy_bytes(void *dst, const void *src, uint64_t nbytes, int threads)
 {
     if (threads <= 1) {
@@ -248,6 +269,19 @@ void cfo_copy_bytes(void *dst, const void *src, uint64_t nbytes, int threads)
         uint64_t hi = (p == threads - 1) ? nbytes : nbytes / (uint64_t)threads * (uint64_t)(p + 1);
         memcpy((char *)dst + lo, (const char *)src + lo, hi - lo);
     }
+}
+
+/* One slice of a replica refresh (section "CheckFree+: First and Last Stage
+ * Recovery", last paragraph: the neighbouring stages hold copies of the
+ * embedding and de-embedding layers; a copy stays current only if it is made
+ * again every iteration, and it may be made piece by piece): `count` elements
+ * of `elem_bytes` bytes each, from element `first` on, carried from src to dst;
+ * every other byte of dst stays as it was. */
+void cfo_copy_range(void *dst, const void *src, uint64_t first, uint64_t count, uint32_t elem_bytes)
+{
+    const char *s = (const char *)src + first * elem_bytes;
+    char *d = (char *)dst + first * elem_bytes;
+    for (uint64_t k = 0; k < count * elem_bytes; ++k) d[k] = s[k];
 }
 
 int cfo_max_threads(void)

@@ -4,6 +4,7 @@ restored from its neighbour and the (de)embedding "exactly")."""
 from fractions import Fraction
 
 import numpy as np
+import pytest
 
 import exactmath as em
 import oracle
@@ -65,3 +66,29 @@ def test_copy_equals_weighted_average_with_zero_weight():
     a = rng.normal(0, 0.02, 1000).astype(np.float32)
     b = rng.normal(0, 0.02, 1000).astype(np.float32)
     assert np.array_equal(oracle.copy_stage([a])[0], oracle.recover_stage_weighted_avg([a], [b], 2.0, 0.0)[0])
+
+
+def test_range_copy_moves_the_named_elements_and_nothing_else():
+    """Slices of a replica refresh: numpy's own slice assignment is the reference."""
+    rng = np.random.default_rng(3)
+    src = [rng.integers(0, 2 ** 32, size=5000, dtype=np.uint64).astype(np.uint32).view(np.float32),
+           rng.integers(0, 2 ** 16, size=777, dtype=np.uint64).astype(np.uint16),
+           np.zeros(0, np.float32)]
+    ranges = [(0, 0, 1), (0, 17, 1000), (0, 4999, 1), (1, 3, 0), (1, 700, 77)]
+    dst = [np.full(5000, np.nan, np.float32), np.full(777, 0xABCD, np.uint16), np.zeros(0, np.float32)]
+    want = [d.copy() for d in dst]
+    for t, first, count in ranges:
+        want[t][first:first + count] = src[t][first:first + count]
+    got = oracle.copy_stage_ranges(src, dst, ranges)
+    for g, w in zip(got, want):
+        assert g.tobytes() == w.tobytes()
+    assert np.isnan(got[0][1:17]).all() and np.isnan(got[0][1017:4999]).all()       # guard bands untouched
+    assert (got[1][:700] == 0xABCD).all()
+    # ranges that tile every tensor add up to the whole-stage copy
+    dst2 = [np.zeros_like(s) for s in src]
+    tiles = [(0, lo, min(1024, 5000 - lo)) for lo in range(0, 5000, 1024)] + [(1, 0, 400), (1, 400, 377)]
+    got2 = oracle.copy_stage_ranges(src, dst2, tiles)
+    for g, w in zip(got2, oracle.copy_stage(src)):
+        assert g.tobytes() == w.tobytes()
+    with pytest.raises(ValueError):
+        oracle.copy_stage_ranges(src, dst2, [(1, 700, 78)])

@@ -267,3 +267,66 @@ def test_mismatched_stages_are_rejected():
         oracle.recover_stage_weighted_avg(a, a + a, 1, 1)
     with pytest.raises(ValueError):
         oracle.recover_stage_weighted_avg(a, [np.zeros(4, np.uint16)], 1, 1)
+
+
+# ----------------------------------------------------------------------------
+# the common power-of-two factor taken out of the weights before the blend
+# ----------------------------------------------------------------------------
+
+def test_common_scale_is_an_exact_power_of_two_that_normalises_the_sum():
+    rng = np.random.default_rng(31)
+    for _ in range(300):
+        wp, wn = (10.0 ** rng.uniform(-300, 300, 2)).tolist()
+        if rng.random() < 0.2:
+            wn = 0.0
+        sp, sn = oracle.common_scale(wp, wn)
+        assert 1.0 <= sp + sn < 2.0
+        (big, sbig), (small, ssmall) = sorted([(wp, sp), (wn, sn)], reverse=True)
+        f = Fraction(sbig) / Fraction(big)
+        assert f.numerator == 1 or f.denominator == 1                      # a power of two ...
+        assert (f.numerator & (f.numerator - 1)) == 0 and (f.denominator & (f.denominator - 1)) == 0
+        # ... and the same one on both weights, unless the smaller one was pushed below the binary64
+        # range, where it is more than 2^1000 times smaller than the other and cannot matter
+        assert Fraction(ssmall) == Fraction(small) * f or ssmall < 2.0 ** -1000
+    assert oracle.common_scale(1.0, 0.5) == (1.0, 0.5)                      # already in [1, 2): untouched
+    assert oracle.common_scale(3.0, 1.0) == (0.75, 0.25)
+
+
+@pytest.mark.parametrize("dtype", ["f32", "bf16"])
+def test_scale_invariance_in_omega_over_the_whole_binary64_range(dtype):
+    """The equation does not change under a common factor; with the factor taken
+    out first the result is the same bits from one end of the range to the other."""
+    rng = np.random.default_rng(32)
+    a, b = _rand_weights(rng, 3000, dtype)
+    wp, wn = 3.7e-3, 1.9e-2
+    ref = oracle.recover_stage_weighted_avg([a], [b], wp, wn)[0]
+    for k in (-1000, -960, -500, 500, 1000, 1020):
+        out = oracle.recover_stage_weighted_avg([a], [b], wp * 2.0 ** k, wn * 2.0 ** k)[0]
+        assert np.array_equal(out, ref), k
+
+
+@pytest.mark.parametrize("dtype", ["f32", "bf16"])
+def test_exact_rational_brute_force_at_extreme_omegas(dtype):
+    """Omegas near the ends of the binary64 range against weights of ordinary and
+    of extreme size: the exact value of the equation, correctly rounded."""
+    rng = np.random.default_rng(33)
+    worst = 0
+    pairs = [(1e300, 3e299), (2e-300, 7e-301), (1.5e-310, 4e-307), (8e307, 1e305), (1e300, 1e-300)]
+    a, b = _rand_weights(rng, 60, dtype)
+    if dtype == "f32":
+        a[:4] = [3e38, -1e-38, 1e-45, 2.5]
+        b[:4] = [-2e38, 1e-38, -3e-45, 1e30]
+    for wp, wn in pairs:
+        out = oracle.recover_stage_weighted_avg([a], [b], wp, wn)[0]
+        for k in range(a.size):
+            if dtype == "f32":
+                fa, fb = Fraction(float(a[k])), Fraction(float(b[k]))
+            else:
+                fa, fb = em.bf16_bits_to_fraction(a[k]), em.bf16_bits_to_fraction(b[k])
+            exact = (Fraction(wp) * fa + Fraction(wn) * fb) / (Fraction(wp) + Fraction(wn))
+            if dtype == "f32":
+                want = np.array([em.fraction_to_f32_bits(exact)], np.uint32).view(np.float32)
+            else:
+                want = np.array([em.fraction_to_bf16_bits(exact)], np.uint16)
+            worst = max(worst, int(em.ulp_distance(out[k:k + 1], want)[0]))
+    assert worst <= 1

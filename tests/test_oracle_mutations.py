@@ -44,6 +44,13 @@ MUTANTS = [
     ("weights: zero omega on one side treated as unusable", "omega_next >= 0.0 && isfinite(d)", "omega_next > 0.0 && isfinite(d)"),
     ("weights: negative omega accepted", "omega_prev >= 0.0 &&", "1 &&"),
     ("weights: zero sum accepted", "d >= 2.2250738585072014e-308", "d >= 0.0"),
+    ("common scale: only one weight scaled", "*wn = ldexp(*wn, 1 - e);", ""),
+    ("common scale: factor inverted (sum driven out of range instead of into [1, 2))", "*wp = ldexp(*wp, 1 - e);\n    *wn = ldexp(*wn, 1 - e);",
+     "*wp = ldexp(*wp, e - 1);\n    *wn = ldexp(*wn, e - 1);"),
+    ("common scale: left out of the fp32 blend", "cfo_common_scale(&wp, &wn);\n    if (threads < 1) threads = 1;\n#pragma omp parallel for num_threads(threads) schedule(static)\n    for (uint64_t k = 0; k < n; ++k)\n        out[k] = (float)",
+     "if (threads < 1) threads = 1;\n#pragma omp parallel for num_threads(threads) schedule(static)\n    for (uint64_t k = 0; k < n; ++k)\n        out[k] = (float)"),
+    ("range copy: source read from element 0", "const char *s = (const char *)src + first * elem_bytes;", "const char *s = (const char *)src;"),
+    ("range copy: count taken as bytes", "for (uint64_t k = 0; k < count * elem_bytes; ++k) d[k] = s[k];", "for (uint64_t k = 0; k < count; ++k) d[k] = s[k];"),
     ("copy: one byte short", "memcpy(dst, src, nbytes);\n        return;", "memcpy(dst, src, nbytes ? nbytes - 1 : 0);\n        return;"),
 ]
 
