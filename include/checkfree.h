@@ -4,7 +4,7 @@
  *
  * Paper: "All is Not Lost: LLM Recovery without Checkpoints" (CheckFree /
  * CheckFree+).  A pipeline *stage* S_i holds a consecutive block of layers; its
- * weights W^S_i are "the combination of weights of the layers in that stage"
+ * weights W^S_i are all the weight tensors of those layers taken together
  * (section "Problem Statement", paragraph "Distributed Training").  Here a stage
  * is an ordered list of contiguous device tensors.
  *
@@ -20,24 +20,34 @@
  *
  *   cf_copy_stage                  W^S_dst = W^S_src, bit for bit
  *       (section "CheckFree+: First and Last Stage Recovery": a first/last stage
- *       is restored from its neighbour, embedding and de-embedding from the
- *       replicas kept on the neighbouring stages, "exactly")
+ *       is restored from its neighbour, embedding and de-embedding without any
+ *       loss from the replicas kept on the neighbouring stages)
  *
  * General rules
  *   - Every function returns a cf_status (0 = CF_OK, negative = error) and never
  *     throws, aborts or exits.  Nothing is launched when an error is returned.
  *   - Pointers named d_* and every cf_tensor.data are DEVICE pointers; everything
  *     else is a HOST pointer.
- *   - The library never allocates, frees or keeps alive tensor memory.  Handles
- *     own only small tables (a few KB to a few hundred KB of device memory,
- *     allocated when the handle is created).  The three hot calls allocate
- *     nothing, copy nothing between host and device, and do not synchronise:
- *     they enqueue work on the caller's stream and return.
+ *   - The library never allocates, frees or keeps alive tensor memory.  A handle
+ *     needs a small device block (a context 256 bytes; a stage 24 bytes per
+ *     chunk and 4 per tensor: about 150 KB for a 1.5B-parameter-model stage).
+ *     With cf_ctx_create_in / cf_stage_create_in that block is the caller's
+ *     (sized by cf_workspace_bytes / cf_stage_table_bytes) and creating a
+ *     handle allocates no device memory, copies nothing between host and
+ *     device and waits for nothing: it enqueues one small kernel per 128
+ *     tensors on the caller's stream.  cf_ctx_create / cf_stage_create are the
+ *     same calls on a block the library allocates itself, followed by a wait.
+ *   - The hot calls allocate nothing, copy nothing between host and device,
+ *     and do not synchronise: they enqueue work on the caller's stream and
+ *     return.
  *   - `stream` is a hipStream_t passed as void* (NULL = the default stream).
- *   - Calls may be issued on any streams.  The only shared device state is the
- *     context's flag word (updated atomically) and, per stage handle, the
- *     scratch of cf_stage_grad_sqnorm: the same gradient-stage handle must not be
- *     in two cf_stage_grad_sqnorm calls that may run at the same time.
+ *   - Calls may be issued on any streams.  A stage handle made by
+ *     cf_stage_create_in is usable by work that is ordered after the stream it
+ *     was created on (the same stream, or after a wait on it).  The only shared
+ *     device state is the context's flag word (updated atomically) and, per
+ *     stage handle, the scratch of cf_stage_grad_sqnorm inside the stage's
+ *     block: the same gradient-stage handle must not be in two
+ *     cf_stage_grad_sqnorm calls that may run at the same time.
  *   - Entry points may be called from several host threads; a handle must not be
  *     destroyed while another thread still uses it.
  *   - Data-dependent conditions cannot be returned synchronously; they raise
@@ -96,7 +106,8 @@ typedef struct cf_tensor {
 
 /* Launch shape knobs.  Zero in any field keeps the default. */
 typedef struct cf_tuning {
-    uint32_t chunk_bytes;          /* bytes per work chunk: a power of two, 4 KiB .. 4 MiB (default 128 KiB) */
+    uint32_t chunk_bytes;          /* bytes per work chunk: a power of two, 4 KiB .. 4 MiB (default 128 KiB);
+                                      results of the norm differ between chunk sizes only in the last bits */
     uint32_t sqnorm_blocks_per_cu; /* cap on the norm's first-pass grid, in workgroups per compute unit;
                                       default 0 = one workgroup per chunk; at most 64 */
     uint32_t reserved0;
@@ -106,31 +117,65 @@ typedef struct cf_tuning {
 typedef struct cf_ctx cf_ctx;      /* opaque: per-device bookkeeping */
 typedef struct cf_stage cf_stage;  /* opaque: a stage's tensor list, uploaded once */
 
-/* ---- set-up (not on the hot path; may allocate small device tables and
- *      synchronise) ---- */
+/* ---- set-up in caller-provided device memory: allocates no device memory,
+ *      copies nothing, never synchronises ---- */
 
-/* Creates a context on HIP device `device`.  `tuning` may be NULL.  Allocates a
- * 256-byte device word block (flags).  Errors: CF_ERR_NULL, CF_ERR_HIP,
- * CF_ERR_LIMIT (bad tuning value). */
+/* Bytes of device memory a context needs (its word block: sticky flags). */
+CF_API uint64_t cf_workspace_bytes(void);
+
+/* Creates a context on HIP device `device` whose word block is the caller's
+ * DEVICE memory `d_workspace` (at least cf_workspace_bytes() bytes, 16-byte
+ * aligned, alive and untouched by others until cf_ctx_destroy).  One small
+ * kernel on `stream` clears it; work that uses the context must be ordered
+ * after that.  `tuning` may be NULL.
+ * Errors: CF_ERR_NULL, CF_ERR_ALIGN, CF_ERR_LIMIT (workspace too small, bad
+ * tuning value), CF_ERR_HIP. */
+CF_API cf_status cf_ctx_create_in(int device, const cf_tuning *tuning, void *d_workspace,
+                                  uint64_t workspace_bytes, void *stream, cf_ctx **out);
+
+/* Bytes of device memory the tables of a stage with these tensors need under
+ * `ctx`'s chunk size (0 for a stage without tensors).  UINT64_MAX if the list
+ * would be refused by cf_stage_create_in. */
+CF_API uint64_t cf_stage_table_bytes(const cf_ctx *ctx, const cf_tensor *tensors, uint32_t num_tensors);
+
+/* Describes a stage (paper, section "Problem Statement": a stage's weights are
+ * the weight tensors of its layers; Algorithm 1, the two "Receive" steps, is
+ * where a joining node first holds its neighbours' stages and needs handles
+ * for them): `tensors` is a HOST array of `num_tensors` descriptors, borrowed
+ * only for the duration of this call.  The tensors' memory is borrowed for as
+ * long as the stage handle is used; the caller keeps it alive and at the same
+ * addresses.  The stage's tables are written into the caller's DEVICE memory
+ * `d_table` (at least cf_stage_table_bytes() bytes, 16-byte aligned, alive and
+ * untouched by others until cf_stage_destroy; may be NULL when that size is 0)
+ * by small kernels enqueued on `stream`, fed from their argument blocks (128
+ * tensors per launch).  num_tensors may be 0.
+ * Errors: CF_ERR_NULL, CF_ERR_DTYPE, CF_ERR_ALIGN, CF_ERR_LIMIT (table_bytes
+ * too small, a tensor above 2^40 elements, or a stage above 2^31 - 1 one-KiB
+ * tiles, about 2 TiB), CF_ERR_HIP. */
+CF_API cf_status cf_stage_create_in(cf_ctx *ctx, const cf_tensor *tensors, uint32_t num_tensors, void *d_table,
+                                    uint64_t table_bytes, void *stream, cf_stage **out);
+
+/* ---- the same set-up on memory the library allocates (convenience; these two
+ *      call hipMalloc and wait for the set-up kernels) ---- */
+
+/* cf_ctx_create_in on a block of cf_workspace_bytes() bytes from hipMalloc,
+ * ready on return.  Errors: CF_ERR_NULL, CF_ERR_HIP, CF_ERR_LIMIT (bad tuning
+ * value). */
 CF_API cf_status cf_ctx_create(int device, const cf_tuning *tuning, cf_ctx **out);
 
-/* Frees the context's device words.  Stages created from it must be destroyed
- * first: while any is alive this returns CF_ERR_CONTEXT and frees nothing.
- * NULL is accepted. */
+/* Destroys the context (and frees its word block if the library allocated it).
+ * Stages created from it must be destroyed first: while any is alive this
+ * returns CF_ERR_CONTEXT and frees nothing.  NULL is accepted. */
 CF_API cf_status cf_ctx_destroy(cf_ctx *ctx);
 
-/* Describes a stage: `tensors` is a HOST array of `num_tensors` descriptors,
- * borrowed only for the duration of this call (its contents are copied).  The
- * tensors' memory is borrowed for as long as the stage handle is used; the
- * caller keeps it alive and at the same addresses.  num_tensors may be 0.
- * Allocates the stage's device tables (20 bytes per chunk, 4 bytes per tensor)
- * and uploads them with blocking host-to-device copies.
- * Errors: CF_ERR_NULL, CF_ERR_DTYPE, CF_ERR_ALIGN, CF_ERR_LIMIT (a tensor above
- * 2^40 elements, or a stage above 2^31 - 1 one-KiB tiles, about 2 TiB),
- * CF_ERR_HIP. */
+/* cf_stage_create_in on a block of cf_stage_table_bytes() bytes from hipMalloc,
+ * on the default stream, ready for use on any stream on return.  Errors as for
+ * cf_stage_create_in. */
 CF_API cf_status cf_stage_create(cf_ctx *ctx, const cf_tensor *tensors, uint32_t num_tensors, cf_stage **out);
 
-/* Frees the stage's tables (never the tensors).  NULL is accepted. */
+/* Destroys the handle (never the tensors; the tables only if the library
+ * allocated them).  Work that uses the handle must have finished.  NULL is
+ * accepted. */
 CF_API cf_status cf_stage_destroy(cf_stage *stage);
 
 /* Introspection; 0 for a NULL handle. */
@@ -149,14 +194,20 @@ CF_API uint32_t cf_stage_num_chunks(const cf_stage *stage);
  *   grad_stages  HOST array of n_stages stage handles (tensors CF_F32 or CF_BF16)
  *   d_omega_out  DEVICE array of n_stages doubles, written by the kernel
  *
- * Elements are squared and accumulated in binary32 per lane, reduced per
- * wavefront and then per workgroup (through LDS) to one binary32 partial per
- * chunk at a fixed slot, and the partials of a stage are summed in binary64 in a fixed order by a second,
- * tiny kernel enqueued right behind the first: the result is bit-identical from
- * run to run and does not depend on the grid size.  An empty stage gives 0.  A non-finite result
- * raises CF_FLAG_NONFINITE_OMEGA.  The same stage handle must not appear in two
- * sqnorm calls that run concurrently (each handle owns its partial-sum scratch:
- * 4 bytes per chunk, allocated by cf_stage_create).
+ * Every element is widened to binary64, squared and accumulated there per
+ * lane, reduced per wavefront (cross-lane moves) and then per workgroup
+ * (through LDS) to one binary64 partial per chunk at a fixed slot, and the
+ * partials of a stage are summed in a fixed order by a second, tiny kernel
+ * enqueued right behind the first: the result is bit-identical from run to run
+ * and does not depend on the grid size.  Squares of binary32 values neither
+ * underflow nor overflow in binary64, and the relative error of omega is below
+ * 1e-10 for every stage size and every accepted tuning (all terms are
+ * non-negative, so it is at most the length of the longest chain of additions,
+ * at most 2^19, times 2^-53; about 1e-14 for a 1.5B-parameter-model stage).  An
+ * empty stage gives 0.  A non-finite result (a NaN or Inf gradient) raises
+ * CF_FLAG_NONFINITE_OMEGA.  The same stage handle must not appear in two
+ * sqnorm calls that run concurrently (each handle's block holds its
+ * partial-sum scratch, 8 bytes per chunk).
  * Errors: CF_ERR_NULL, CF_ERR_CONTEXT, CF_ERR_LIMIT, CF_ERR_HIP. */
 CF_API cf_status cf_stage_grad_sqnorm(cf_ctx *ctx, const cf_stage *const *grad_stages, uint32_t n_stages,
                                double *d_omega_out, void *stream);
@@ -187,7 +238,10 @@ CF_API cf_status cf_stage_grad_sqnorm_per_tensor(cf_ctx *ctx, const cf_stage *gr
  * Arithmetic per element: both products and their sum in binary64, each rounded
  * separately (no fused multiply-add), times the binary64 reciprocal of
  * (w_p + w_n), one rounding (nearest even) to the tensor's dtype.  Subnormals are
- * kept.
+ * kept.  Before that both weights are multiplied by the power of two that brings
+ * their sum into [1, 2) (exact, and the equation does not change under a common
+ * factor), so no product leaves the binary64 range however large or small the
+ * omegas are.
  *
  * If the pair is unusable -- either omega negative, NaN or Inf, or their sum not
  * a positive normal binary64 number -- both weights are replaced by 1 (the
@@ -224,10 +278,27 @@ CF_API cf_status cf_recover_stage_with_weights(cf_ctx *ctx, const cf_stage *prev
  * CF_ERR_HIP. */
 CF_API cf_status cf_copy_stage(cf_ctx *ctx, const cf_stage *src, cf_stage *dst, void *stream);
 
+/* The same copy for the chunks first_chunk .. first_chunk + n_chunks - 1 of the
+ * stage only (chunks as cf_plan_chunks lists them for the context's chunk size;
+ * cf_stage_num_chunks of them in all); every other byte of dst is left as it
+ * is.  Paper: section "CheckFree+: First and Last Stage Recovery", last
+ * paragraph: the embedding and de-embedding layers are kept as replicas on the
+ * neighbouring stages so that they can be restored without loss; keeping such a
+ * replica current means copying it again every iteration, and this call lets
+ * that copy be issued in slices, on a side stream, between the compute-bound
+ * kernels of a training step instead of as one bandwidth-bound block.
+ * Errors: as cf_copy_stage, and CF_ERR_LIMIT if the range reaches past the
+ * stage's last chunk. */
+CF_API cf_status cf_copy_stage_range(cf_ctx *ctx, const cf_stage *src, cf_stage *dst, uint32_t first_chunk,
+                                     uint32_t n_chunks, void *stream);
+
 /* ---- after the fact ---- */
 
-/* Waits for `stream`, then copies the context's sticky flag word to *flags
- * (HOST).  If `clear` is non-zero the device word is reset to 0 afterwards.
+/* Enqueues a one-thread kernel on `stream` that reads the context's sticky flag
+ * word and, if `clear` is non-zero, resets it to 0 in the same atomic
+ * operation (a flag raised meanwhile by work on another stream is either
+ * reported now or kept for the next read); waits for `stream`; stores the value
+ * in *flags (HOST).  One cf_read_flags at a time per context.
  * Errors: CF_ERR_NULL, CF_ERR_HIP. */
 CF_API cf_status cf_read_flags(cf_ctx *ctx, void *stream, uint32_t *flags, int clear);
 

@@ -38,6 +38,8 @@ EXPORTS = (
     "cf_plan_num_chunks", "cf_plan_chunks", "cf_default_tuning", "cf_status_string",
     "cf_recover_stage_with_weights", "cf_recovered_learning_rate", "cf_check_stage_pair",
     "cf_stage_grad_sqnorm_per_tensor",
+    "cf_workspace_bytes", "cf_ctx_create_in", "cf_stage_table_bytes", "cf_stage_create_in",
+    "cf_copy_stage_range",
 )
 
 
@@ -78,6 +80,16 @@ def load_library():
     vp, u32, u64, i32 = ctypes.c_void_p, ctypes.c_uint32, ctypes.c_uint64, ctypes.c_int32
     lib.cf_ctx_create.restype = i32
     lib.cf_ctx_create.argtypes = [ctypes.c_int, ctypes.POINTER(CfTuning), ctypes.POINTER(vp)]
+    lib.cf_workspace_bytes.restype = u64
+    lib.cf_workspace_bytes.argtypes = []
+    lib.cf_ctx_create_in.restype = i32
+    lib.cf_ctx_create_in.argtypes = [ctypes.c_int, ctypes.POINTER(CfTuning), vp, u64, vp, ctypes.POINTER(vp)]
+    lib.cf_stage_table_bytes.restype = u64
+    lib.cf_stage_table_bytes.argtypes = [vp, ctypes.POINTER(CfTensor), u32]
+    lib.cf_stage_create_in.restype = i32
+    lib.cf_stage_create_in.argtypes = [vp, ctypes.POINTER(CfTensor), u32, vp, u64, vp, ctypes.POINTER(vp)]
+    lib.cf_copy_stage_range.restype = i32
+    lib.cf_copy_stage_range.argtypes = [vp, vp, vp, u32, u32, vp]
     lib.cf_ctx_destroy.restype = i32
     lib.cf_ctx_destroy.argtypes = [vp]
     lib.cf_stage_create.restype = i32
@@ -168,9 +180,14 @@ def tensor_descriptors(tensors):
 
 
 class Context:
-    """cf_ctx: per-device bookkeeping (launch shape, sticky flag word)."""
+    """cf_ctx: per-device bookkeeping (launch shape, sticky flag word).
 
-    def __init__(self, device=0, **tuning):
+    By default the context's device word block is a torch allocation handed to
+    cf_ctx_create_in (nothing is allocated by the library, nothing waited for;
+    the block is cleared by a kernel on `stream`).  owned=True lets the library
+    allocate it (cf_ctx_create)."""
+
+    def __init__(self, device=0, owned=False, stream=None, **tuning):
         import torch
         self._h = ctypes.c_void_p()
         self.device = torch.device("cuda", device) if isinstance(device, int) else torch.device(device)
@@ -178,9 +195,16 @@ class Context:
         self.device = torch.device("cuda", index)
         self._stages = weakref.WeakSet()
         t = CfTuning(**{k: int(v) for k, v in tuning.items()}) if tuning else None
+        tp = ctypes.byref(t) if t is not None else None
         lib = load_library()
-        _check(lib.cf_ctx_create(index, ctypes.byref(t) if t is not None else None, ctypes.byref(self._h)),
-               "cf_ctx_create")
+        self.workspace = None
+        if owned or not torch.cuda.is_available():
+            _check(lib.cf_ctx_create(index, tp, ctypes.byref(self._h)), "cf_ctx_create")
+        else:
+            nbytes = int(lib.cf_workspace_bytes())
+            self.workspace = torch.empty(nbytes, dtype=torch.uint8, device=self.device)
+            _check(lib.cf_ctx_create_in(index, tp, ctypes.c_void_p(self.workspace.data_ptr()), nbytes,
+                                        _stream_ptr(stream), ctypes.byref(self._h)), "cf_ctx_create_in")
 
     def read_flags(self, clear=False, stream=None) -> int:
         out = ctypes.c_uint32(0)
@@ -211,18 +235,42 @@ class Context:
 
 class Stage:
     """cf_stage: the tensor list of one pipeline stage (weights or gradients).
-    Keeps the tensors alive; the library only borrows their memory."""
+    Keeps the tensors alive; the library only borrows their memory.
 
-    def __init__(self, ctx: Context, tensors):
+    By default the stage's device tables live in a torch allocation handed to
+    cf_stage_create_in: creating the handle allocates nothing in the library,
+    copies nothing and waits for nothing; the tables are written by a small
+    kernel on `stream` (default: the current stream), and work that uses the
+    stage must be ordered after it.  `table` is an existing uint8 device
+    tensor of at least stage_table_bytes(ctx, tensors) bytes to use instead of a
+    new one.  owned=True lets the library allocate the tables and wait
+    (cf_stage_create)."""
+
+    def __init__(self, ctx: Context, tensors, owned=False, stream=None, table=None):
+        import torch
         self.ctx = ctx
         self.tensors = list(tensors)
         for t in self.tensors:
             if t.device != ctx.device:
                 raise ValueError(f"tensor on {t.device}, context on {ctx.device}")
         self._h = ctypes.c_void_p()
+        self.table = None
         desc = tensor_descriptors(self.tensors)
-        _check(load_library().cf_stage_create(ctx._h, desc, len(self.tensors), ctypes.byref(self._h)),
-               "cf_stage_create")
+        lib = load_library()
+        if owned:
+            _check(lib.cf_stage_create(ctx._h, desc, len(self.tensors), ctypes.byref(self._h)), "cf_stage_create")
+        else:
+            nbytes = int(lib.cf_stage_table_bytes(ctx._h, desc, len(self.tensors)))
+            if nbytes == 2 ** 64 - 1:
+                nbytes = 0          # an invalid list: cf_stage_create_in names the reason
+            if table is None:
+                table = torch.empty(nbytes, dtype=torch.uint8, device=ctx.device)
+            elif table.dtype != torch.uint8 or not table.is_contiguous() or table.device != ctx.device:
+                raise ValueError("table must be a contiguous uint8 tensor on the context's device")
+            self.table = table
+            _check(lib.cf_stage_create_in(ctx._h, desc, len(self.tensors),
+                                          ctypes.c_void_p(table.data_ptr() if table.numel() else None), table.numel(),
+                                          _stream_ptr(stream), ctypes.byref(self._h)), "cf_stage_create_in")
         ctx._stages.add(self)
 
     def __repr__(self):
@@ -250,6 +298,15 @@ class Stage:
             self.close()
         except Exception:
             pass
+
+
+def stage_table_bytes(ctx: Context, tensors) -> int:
+    """Bytes of device memory cf_stage_create_in needs for a stage of these tensors."""
+    desc = tensor_descriptors(list(tensors))
+    n = int(load_library().cf_stage_table_bytes(ctx._h, desc, len(tensors)))
+    if n == 2 ** 64 - 1:
+        raise CheckFreeError(CF_ERR_LIMIT, "cf_stage_table_bytes")
+    return n
 
 
 def cf_stage_grad_sqnorm(ctx: Context, grad_stages, out=None, stream=None):
@@ -316,6 +373,14 @@ def cf_recovered_learning_rate(learning_rate: float) -> float:
 def cf_copy_stage(ctx: Context, src: Stage, dst: Stage, stream=None):
     """dst <- src bit for bit (CheckFree+ end-stage / (de)embedding recovery)."""
     _check(load_library().cf_copy_stage(ctx._h, src._h, dst._h, _stream_ptr(stream)), "cf_copy_stage")
+    return dst
+
+
+def cf_copy_stage_range(ctx: Context, src: Stage, dst: Stage, first_chunk: int, n_chunks: int, stream=None):
+    """dst <- src for chunks first_chunk .. first_chunk + n_chunks - 1 only (a slice of
+    a replica refresh); the rest of dst is left as it is."""
+    _check(load_library().cf_copy_stage_range(ctx._h, src._h, dst._h, int(first_chunk), int(n_chunks),
+                                              _stream_ptr(stream)), "cf_copy_stage_range")
     return dst
 
 

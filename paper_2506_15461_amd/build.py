@@ -12,7 +12,8 @@ PKG = os.path.dirname(os.path.abspath(__file__))
 ROOT = os.path.dirname(PKG)
 CSRC = os.path.join(PKG, "csrc")
 LIB = os.path.join(PKG, "libcheckfree.so")
-SOURCES = ["cf_kernels.hip", "cf_api.cpp"]
+HIP_SOURCES = ["cf_kernels.hip"]
+HOST_SOURCES = ["cf_api.cpp"]
 
 
 def hipcc_path():
@@ -22,25 +23,54 @@ def hipcc_path():
     return "hipcc"
 
 
-def command(out=LIB, extra=()):
-    return [
-        hipcc_path(), "--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-shared",
-        "-ffp-contract=off", "-fvisibility=hidden",
-        "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops",
-        "-Wall", "-Wextra", "-Wno-unused-parameter",
-        "-I", os.path.join(ROOT, "include"), "-I", CSRC,
-        *[os.path.join(CSRC, s) for s in SOURCES],
-        *extra,
-        "-o", out,
-    ]
+# hipcc compiles a .hip file once per offload target and once for the host; the host pass does not
+# know this device-only feature and says so on stderr (harmless; that exact line is dropped below).
+NO_PACKED_FP32 = ["-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops"]
+HOST_PASS_NOTE = "'-packed-fp32-ops' is not a recognized feature for this target (ignoring feature)"
+COMMON = ["-O3", "-std=c++17", "-fPIC", "-ffp-contract=off", "-fvisibility=hidden", "-Wall", "-Wextra",
+          "-Wno-unused-parameter", "-I", os.path.join(ROOT, "include"), "-I", CSRC]
 
 
-def build(verbose=True):
-    cmd = command()
+def rocm_path():
+    return os.environ.get("ROCM_PATH", "/opt/rocm")
+
+
+def commands(objdir, out=LIB, extra=()):
+    """Device code (the .hip files) with packed-FP32 selection off; the host-only C ABI file as plain
+    C++ (it has no device code); then the link."""
+    hipcc = hipcc_path()
+    cmds, objs = [], []
+    for src in HIP_SOURCES:
+        obj = os.path.join(objdir, src + ".o")
+        cmds.append([hipcc, "--offload-arch=gfx950", *COMMON, *NO_PACKED_FP32, *extra, "-c",
+                     os.path.join(CSRC, src), "-o", obj])
+        objs.append(obj)
+    for src in HOST_SOURCES:
+        obj = os.path.join(objdir, src + ".o")
+        cmds.append([hipcc, "-x", "c++", "-D__HIP_PLATFORM_AMD__", "-isystem", os.path.join(rocm_path(), "include"),
+                     *COMMON, *extra, "-c", os.path.join(CSRC, src), "-o", obj])
+        objs.append(obj)
+    cmds.append([hipcc, "--offload-arch=gfx950", "-shared", "-fPIC", *extra, *objs, "-o", out])
+    return cmds
+
+
+def run(cmd, verbose=True):
     if verbose:
         print(" ".join(cmd), flush=True)
-    subprocess.run(cmd, check=True)
-    return LIB
+    r = subprocess.run(cmd, stderr=subprocess.PIPE, text=True)
+    noise = [l for l in r.stderr.splitlines() if l.strip() and l.strip() != HOST_PASS_NOTE]
+    if noise:
+        print("\n".join(noise), file=sys.stderr, flush=True)
+    if r.returncode != 0:
+        raise subprocess.CalledProcessError(r.returncode, cmd)
+
+
+def build(verbose=True, out=LIB, extra=()):
+    import tempfile
+    with tempfile.TemporaryDirectory(prefix="cf_build_") as objdir:
+        for cmd in commands(objdir, out, extra):
+            run(cmd, verbose)
+    return out
 
 
 C_SMOKE_SRC = os.path.join(ROOT, "tests", "c_abi_smoke.c")

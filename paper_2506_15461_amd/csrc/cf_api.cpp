@@ -21,7 +21,8 @@ constexpr uint32_t kMaxChunkBytes = 4u << 20;
 constexpr uint32_t kDefaultSqnormBlocksPerCu = 0;     // 0: one workgroup per chunk
 constexpr uint64_t kMaxChunksPerStage = 1ull << 31;
 constexpr uint64_t kMaxGrid = (1ull << 31) - 1;
-constexpr size_t kCtxWordBytes = 256;
+constexpr size_t kCtxWordBytes = CF_CTX_WORDS * sizeof(uint32_t);
+constexpr uint64_t kTableAlign = 256;   // sections of a stage's device tables start on multiples of this
 
 std::atomic<uint64_t> g_next_stage_id{1};
 
@@ -41,6 +42,7 @@ struct cf_ctx {
     cf_tuning tuning{};
     uint32_t tile_shift = 0;   // log2(chunk_bytes / CF_TILE_BYTES)
     uint32_t *d_words = nullptr;
+    bool owns_words = false;   // d_words came from hipMalloc here (else it is the caller's workspace)
     std::atomic<uint32_t> live_stages{0};
     // Pairs (input stage id, output stage id) whose congruence and aliasing have been checked.
     std::mutex checked_mutex;
@@ -54,8 +56,10 @@ struct cf_stage {
     uint64_t numel = 0;
     uint64_t nbytes = 0;
     uint32_t n_chunks = 0;
+    void *d_table = nullptr;       // the device block the three tables below live in
+    bool owns_table = false;       // d_table came from hipMalloc here (else it is the caller's)
     CfChunk *d_chunks = nullptr;   // n_chunks entries
-    float *d_partials = nullptr;   // n_chunks floats (sqnorm scratch)
+    double *d_partials = nullptr;  // n_chunks doubles (sqnorm scratch)
     uint32_t *d_tensor_first = nullptr;   // tensors + 1 entries: first chunk of each tensor
 };
 
@@ -92,6 +96,38 @@ cf_status check_tensor(const cf_tensor &t)
 }
 
 uint64_t chunks_of(uint64_t numel, uint64_t chunk_elems) { return (numel + chunk_elems - 1) / chunk_elems; }
+
+uint64_t align_up(uint64_t v) { return (v + kTableAlign - 1) / kTableAlign * kTableAlign; }
+
+// Where a stage's three tables sit inside its device block.
+struct TableLayout {
+    uint64_t chunks_off, first_off, partials_off, total;
+};
+
+TableLayout table_layout(uint64_t n_chunks, uint32_t num_tensors)
+{
+    TableLayout l;
+    l.chunks_off = 0;
+    l.first_off = align_up(n_chunks * sizeof(CfChunk));
+    l.partials_off = l.first_off + (num_tensors ? align_up(((uint64_t)num_tensors + 1) * sizeof(uint32_t)) : 0);
+    l.total = l.partials_off + align_up(n_chunks * sizeof(double));
+    return l;
+}
+
+// Validates a tensor list and counts its chunks.
+cf_status plan_stage(const cf_ctx *ctx, const cf_tensor *tensors, uint32_t num_tensors, uint64_t *n_chunks_out)
+{
+    const uint32_t chunk_bytes = ctx->tuning.chunk_bytes;
+    uint64_t n_chunks = 0;
+    for (uint32_t t = 0; t < num_tensors; ++t) {
+        cf_status st = check_tensor(tensors[t]);
+        if (st != CF_OK) return st;
+        n_chunks += chunks_of(tensors[t].numel, chunk_bytes / elem_size(tensors[t].dtype));
+    }
+    if (n_chunks >= kMaxChunksPerStage || (n_chunks << ctx->tile_shift) > kMaxGrid) return CF_ERR_LIMIT;
+    *n_chunks_out = n_chunks;
+    return CF_OK;
+}
 
 bool valid_chunk_bytes(uint32_t b)
 {
@@ -276,10 +312,16 @@ cf_status cf_check_stage_pair(const cf_tensor *in, uint32_t num_in, const cf_ten
     }
 }
 
-cf_status cf_ctx_create(int device, const cf_tuning *tuning, cf_ctx **out)
+uint64_t cf_workspace_bytes(void) { return kCtxWordBytes; }
+
+cf_status cf_ctx_create_in(int device, const cf_tuning *tuning, void *d_workspace, uint64_t workspace_bytes,
+                           void *stream, cf_ctx **out)
 {
     if (!out) return CF_ERR_NULL;
     *out = nullptr;
+    if (!d_workspace) return CF_ERR_NULL;
+    if (workspace_bytes < kCtxWordBytes) return CF_ERR_LIMIT;
+    if (reinterpret_cast<uint64_t>(d_workspace) % 16 != 0) return CF_ERR_ALIGN;
     cf_tuning t;
     cf_default_tuning(&t);
     if (tuning) {
@@ -301,18 +343,38 @@ cf_status cf_ctx_create(int device, const cf_tuning *tuning, cf_ctx **out)
     ctx->num_cu = num_cu;
     ctx->tuning = t;
     for (uint32_t b = t.chunk_bytes / CF_TILE_BYTES; b > 1; b >>= 1) ++ctx->tile_shift;
-    void *p = nullptr;
-    if (hipMalloc(&p, kCtxWordBytes) != hipSuccess) {
+    ctx->d_words = static_cast<uint32_t *>(d_workspace);
+    if (cf_launch_clear_words(ctx->d_words, static_cast<hipStream_t>(stream)) != hipSuccess) {
         delete ctx;
         return CF_ERR_HIP;
     }
-    if (hipMemset(p, 0, kCtxWordBytes) != hipSuccess || hipDeviceSynchronize() != hipSuccess) {
-        (void)hipFree(p);
-        delete ctx;
-        return CF_ERR_HIP;
-    }
-    ctx->d_words = static_cast<uint32_t *>(p);
     *out = ctx;
+    return CF_OK;
+}
+
+cf_status cf_ctx_create(int device, const cf_tuning *tuning, cf_ctx **out)
+{
+    if (!out) return CF_ERR_NULL;
+    *out = nullptr;
+    if (tuning && ((tuning->chunk_bytes && !valid_chunk_bytes(tuning->chunk_bytes)) || tuning->sqnorm_blocks_per_cu > 64))
+        return CF_ERR_LIMIT;
+    int count = 0;
+    if (hipGetDeviceCount(&count) != hipSuccess || device < 0 || device >= count) return CF_ERR_HIP;
+    DeviceGuard guard(device);
+    if (!guard.ok()) return CF_ERR_HIP;
+    void *p = nullptr;
+    if (hipMalloc(&p, kCtxWordBytes) != hipSuccess) return CF_ERR_HIP;
+    cf_status st = cf_ctx_create_in(device, tuning, p, kCtxWordBytes, nullptr, out);
+    if (st == CF_OK && hipStreamSynchronize(nullptr) != hipSuccess) {
+        delete *out;
+        *out = nullptr;
+        st = CF_ERR_HIP;
+    }
+    if (st != CF_OK) {
+        (void)hipFree(p);
+        return st;
+    }
+    (*out)->owns_words = true;
     return CF_OK;
 }
 
@@ -321,7 +383,7 @@ cf_status cf_ctx_destroy(cf_ctx *ctx)
     if (!ctx) return CF_OK;
     if (ctx->live_stages.load() != 0) return CF_ERR_CONTEXT;   // its stages still point at it: nothing is freed
     cf_status st = CF_OK;
-    {
+    if (ctx->owns_words) {
         DeviceGuard guard(ctx->device);
         if (!guard.ok() || hipFree(ctx->d_words) != hipSuccess) st = CF_ERR_HIP;
     }
@@ -329,78 +391,111 @@ cf_status cf_ctx_destroy(cf_ctx *ctx)
     return st;
 }
 
-cf_status cf_stage_create(cf_ctx *ctx, const cf_tensor *tensors, uint32_t num_tensors, cf_stage **out)
+uint64_t cf_stage_table_bytes(const cf_ctx *ctx, const cf_tensor *tensors, uint32_t num_tensors)
+{
+    if (!ctx || (num_tensors && !tensors)) return UINT64_MAX;
+    uint64_t n_chunks = 0;
+    if (plan_stage(ctx, tensors, num_tensors, &n_chunks) != CF_OK) return UINT64_MAX;
+    return table_layout(n_chunks, num_tensors).total;
+}
+
+cf_status cf_stage_create_in(cf_ctx *ctx, const cf_tensor *tensors, uint32_t num_tensors, void *d_table,
+                             uint64_t table_bytes, void *stream, cf_stage **out)
 {
     if (!ctx || !out || (num_tensors && !tensors)) return CF_ERR_NULL;
     *out = nullptr;
-    const uint32_t chunk_bytes = ctx->tuning.chunk_bytes;
     uint64_t n_chunks = 0;
-    for (uint32_t t = 0; t < num_tensors; ++t) {
-        cf_status st = check_tensor(tensors[t]);
-        if (st != CF_OK) return st;
-        n_chunks += chunks_of(tensors[t].numel, chunk_bytes / elem_size(tensors[t].dtype));
+    cf_status st = plan_stage(ctx, tensors, num_tensors, &n_chunks);
+    if (st != CF_OK) return st;
+    const TableLayout layout = table_layout(n_chunks, num_tensors);
+    if (layout.total) {
+        if (!d_table) return CF_ERR_NULL;
+        if (table_bytes < layout.total) return CF_ERR_LIMIT;
+        if (reinterpret_cast<uint64_t>(d_table) % 16 != 0) return CF_ERR_ALIGN;
     }
-    if (n_chunks >= kMaxChunksPerStage || (n_chunks << ctx->tile_shift) > kMaxGrid) return CF_ERR_LIMIT;
 
     cf_stage *stage = new (std::nothrow) cf_stage;
     if (!stage) return CF_ERR_LIMIT;
     stage->ctx = ctx;
     stage->id = g_next_stage_id.fetch_add(1);
     stage->n_chunks = (uint32_t)n_chunks;
-    std::vector<CfChunk> table;
-    std::vector<uint32_t> tensor_first;
     try {
-        table.reserve(n_chunks);
-        tensor_first.reserve(num_tensors + 1);
         stage->tensors.reserve(num_tensors);
     } catch (...) {
         delete stage;
         return CF_ERR_LIMIT;   // host memory exhausted
     }
+    if (layout.total) {
+        char *base = static_cast<char *>(d_table);
+        stage->d_table = d_table;
+        stage->d_chunks = reinterpret_cast<CfChunk *>(base + layout.chunks_off);
+        stage->d_tensor_first = reinterpret_cast<uint32_t *>(base + layout.first_off);
+        stage->d_partials = reinterpret_cast<double *>(base + layout.partials_off);
+    }
+    // The tensor list travels to the device in kernel argument blocks, CF_TABLE_BATCH tensors at a
+    // time; the kernel writes the chunk table.  Nothing is copied and nothing is waited for.
+    const uint32_t chunk_bytes = ctx->tuning.chunk_bytes;
+    DeviceGuard guard(ctx->device);
+    if (!guard.ok()) {
+        delete stage;
+        return CF_ERR_HIP;
+    }
+    CfTableArgs args;
+    std::memset(&args, 0, sizeof args);
+    args.chunks = stage->d_chunks;
+    args.tensor_first = stage->d_tensor_first;
+    args.chunk_bytes = chunk_bytes;
+    args.end_chunk = (uint32_t)n_chunks;
+    uint64_t first_chunk = 0;
     for (uint32_t t = 0; t < num_tensors; ++t) {
         const cf_tensor &d = tensors[t];
-        HostTensor h{reinterpret_cast<uint64_t>(d.data), d.numel, d.dtype};
-        stage->tensors.push_back(h);
+        stage->tensors.push_back({reinterpret_cast<uint64_t>(d.data), d.numel, d.dtype});
         stage->numel += d.numel;
         stage->nbytes += d.numel * elem_size(d.dtype);
-        const uint64_t chunk_elems = chunk_bytes / elem_size(d.dtype);
-        tensor_first.push_back((uint32_t)table.size());
-        for (uint64_t first = 0; first < d.numel; first += chunk_elems) {
-            CfChunk c;
-            c.addr = h.addr + first * elem_size(d.dtype);
-            c.len = (uint32_t)std::min<uint64_t>(chunk_elems, d.numel - first);
-            c.dtype = (uint32_t)d.dtype;
-            table.push_back(c);
+        CfTableTensor &slot = args.tensor[args.n++];
+        slot.addr = reinterpret_cast<uint64_t>(d.data);
+        slot.numel = d.numel;
+        slot.dtype = (uint32_t)d.dtype;
+        slot.first_chunk = (uint32_t)first_chunk;
+        first_chunk += chunks_of(d.numel, chunk_bytes / elem_size(d.dtype));
+        if (args.n == CF_TABLE_BATCH || t + 1 == num_tensors) {
+            args.last = (t + 1 == num_tensors);
+            if (cf_launch_build_table(args, static_cast<hipStream_t>(stream)) != hipSuccess) {
+                delete stage;
+                return CF_ERR_HIP;
+            }
+            args.tensor_base += args.n;
+            args.n = 0;
         }
-    }
-    tensor_first.push_back((uint32_t)table.size());
-    if (num_tensors) {
-        DeviceGuard guard(ctx->device);
-        void *p = nullptr, *q = nullptr, *r = nullptr;
-        bool ok = guard.ok();
-        ok = ok && hipMalloc(&r, tensor_first.size() * sizeof(uint32_t)) == hipSuccess;
-        ok = ok && hipMemcpy(r, tensor_first.data(), tensor_first.size() * sizeof(uint32_t),
-                             hipMemcpyHostToDevice) == hipSuccess;
-        if (n_chunks) {
-            ok = ok && hipMalloc(&p, n_chunks * sizeof(CfChunk)) == hipSuccess;
-            ok = ok && hipMalloc(&q, n_chunks * sizeof(float)) == hipSuccess;
-            ok = ok && hipMemcpy(p, table.data(), n_chunks * sizeof(CfChunk), hipMemcpyHostToDevice) == hipSuccess;
-            ok = ok && hipMemset(q, 0, n_chunks * sizeof(float)) == hipSuccess;
-        }
-        ok = ok && hipDeviceSynchronize() == hipSuccess;
-        if (!ok) {
-            if (p) (void)hipFree(p);
-            if (q) (void)hipFree(q);
-            if (r) (void)hipFree(r);
-            delete stage;
-            return CF_ERR_HIP;
-        }
-        stage->d_chunks = static_cast<CfChunk *>(p);
-        stage->d_partials = static_cast<float *>(q);
-        stage->d_tensor_first = static_cast<uint32_t *>(r);
     }
     ctx->live_stages.fetch_add(1);
     *out = stage;
+    return CF_OK;
+}
+
+cf_status cf_stage_create(cf_ctx *ctx, const cf_tensor *tensors, uint32_t num_tensors, cf_stage **out)
+{
+    if (!ctx || !out || (num_tensors && !tensors)) return CF_ERR_NULL;
+    *out = nullptr;
+    uint64_t n_chunks = 0;
+    cf_status st = plan_stage(ctx, tensors, num_tensors, &n_chunks);
+    if (st != CF_OK) return st;
+    const uint64_t bytes = table_layout(n_chunks, num_tensors).total;
+    DeviceGuard guard(ctx->device);
+    if (!guard.ok()) return CF_ERR_HIP;
+    void *p = nullptr;
+    if (bytes && hipMalloc(&p, bytes) != hipSuccess) return CF_ERR_HIP;
+    st = cf_stage_create_in(ctx, tensors, num_tensors, p, bytes, nullptr, out);
+    if (st == CF_OK && bytes && hipStreamSynchronize(nullptr) != hipSuccess) {
+        (void)cf_stage_destroy(*out);
+        *out = nullptr;
+        st = CF_ERR_HIP;
+    }
+    if (st != CF_OK) {
+        if (p) (void)hipFree(p);
+        return st;
+    }
+    (*out)->owns_table = true;
     return CF_OK;
 }
 
@@ -410,12 +505,9 @@ cf_status cf_stage_destroy(cf_stage *stage)
     cf_status st = CF_OK;
     forget_stage(stage->ctx, stage->id);
     stage->ctx->live_stages.fetch_sub(1);
-    if (stage->d_chunks || stage->d_partials || stage->d_tensor_first) {
+    if (stage->owns_table && stage->d_table) {
         DeviceGuard guard(stage->ctx->device);
-        if (!guard.ok()) st = CF_ERR_HIP;
-        if (stage->d_chunks && hipFree(stage->d_chunks) != hipSuccess) st = CF_ERR_HIP;
-        if (stage->d_partials && hipFree(stage->d_partials) != hipSuccess) st = CF_ERR_HIP;
-        if (stage->d_tensor_first && hipFree(stage->d_tensor_first) != hipSuccess) st = CF_ERR_HIP;
+        if (!guard.ok() || hipFree(stage->d_table) != hipSuccess) st = CF_ERR_HIP;
     }
     delete stage;
     return st;
@@ -524,19 +616,27 @@ cf_status cf_recover_stage_with_weights(cf_ctx *ctx, const cf_stage *prev, const
 
 double cf_recovered_learning_rate(double learning_rate) { return CF_RECOVERY_LR_FACTOR * learning_rate; }
 
-cf_status cf_copy_stage(cf_ctx *ctx, const cf_stage *src, cf_stage *dst, void *stream)
+cf_status cf_copy_stage_range(cf_ctx *ctx, const cf_stage *src, cf_stage *dst, uint32_t first_chunk,
+                              uint32_t n_chunks, void *stream)
 {
     if (!ctx || !src || !dst) return CF_ERR_NULL;
     if (src->ctx != ctx || dst->ctx != ctx) return CF_ERR_CONTEXT;
     cf_status st = checked_pair(ctx, src, dst);
     if (st != CF_OK) return st;
-    if (dst->n_chunks == 0) return CF_OK;
+    if (first_chunk > dst->n_chunks || n_chunks > dst->n_chunks - first_chunk) return CF_ERR_LIMIT;
+    if (n_chunks == 0) return CF_OK;
     DeviceGuard guard(ctx->device);
     if (!guard.ok()) return CF_ERR_HIP;
-    if (cf_launch_copy(src->d_chunks, dst->d_chunks, dst->n_chunks, ctx->tile_shift,
+    if (cf_launch_copy(src->d_chunks, dst->d_chunks, first_chunk, n_chunks, ctx->tile_shift,
                        static_cast<hipStream_t>(stream)) != hipSuccess)
         return CF_ERR_HIP;
     return CF_OK;
+}
+
+cf_status cf_copy_stage(cf_ctx *ctx, const cf_stage *src, cf_stage *dst, void *stream)
+{
+    if (!ctx || !src || !dst) return CF_ERR_NULL;
+    return cf_copy_stage_range(ctx, src, dst, 0, dst->n_chunks, stream);
 }
 
 cf_status cf_read_flags(cf_ctx *ctx, void *stream, uint32_t *flags, int clear)
@@ -545,13 +645,12 @@ cf_status cf_read_flags(cf_ctx *ctx, void *stream, uint32_t *flags, int clear)
     DeviceGuard guard(ctx->device);
     if (!guard.ok()) return CF_ERR_HIP;
     hipStream_t s = static_cast<hipStream_t>(stream);
+    // One kernel behind everything already on `stream` reads the word, and clears it in the same
+    // atomic operation when asked to, into a second word that is then brought to the host.
+    if (cf_launch_read_flags(ctx->d_words, clear, s) != hipSuccess) return CF_ERR_HIP;
     if (hipStreamSynchronize(s) != hipSuccess) return CF_ERR_HIP;
-    if (hipMemcpy(flags, ctx->d_words + CF_WORD_FLAGS, sizeof(uint32_t), hipMemcpyDeviceToHost) != hipSuccess)
+    if (hipMemcpy(flags, ctx->d_words + CF_WORD_FLAGS_READ, sizeof(uint32_t), hipMemcpyDeviceToHost) != hipSuccess)
         return CF_ERR_HIP;
-    if (clear) {
-        if (hipMemset(ctx->d_words + CF_WORD_FLAGS, 0, sizeof(uint32_t)) != hipSuccess) return CF_ERR_HIP;
-        if (hipDeviceSynchronize() != hipSuccess) return CF_ERR_HIP;
-    }
     return CF_OK;
 }
 

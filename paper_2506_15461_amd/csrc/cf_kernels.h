@@ -24,12 +24,14 @@ constexpr int CF_MAX_SEG = 64;           // stages per sqnorm launch
 constexpr int CF_TILE_THREADS = 64;      // blend/copy: one wavefront per workgroup
 constexpr uint32_t CF_TILE_BYTES = CF_TILE_THREADS * 16u;   // one 16-byte vector per lane: the blend/copy work unit
 
-// Device word block owned by a context.
+// Device word block of a context (CF_CTX_WORDS 32-bit words).
+constexpr int CF_CTX_WORDS = 64;
 constexpr int CF_WORD_FLAGS = 1;         // sticky CF_FLAG_* bits
+constexpr int CF_WORD_FLAGS_READ = 2;    // what the last read-flags kernel saw
 
 struct CfSqnormSeg {
     const CfChunk *chunks;   // the stage's chunk table
-    float *partials;         // one slot per chunk
+    double *partials;        // one slot per chunk
     uint32_t chunk_begin;    // index of the stage's first chunk in the launch
     uint32_t n_chunks;
 };
@@ -42,12 +44,44 @@ struct CfSqnormArgs {
     uint32_t *words;         // context word block
 };
 
+// A stage's tensor list as it travels to the table-building kernel: in the
+// kernel argument block, CF_TABLE_BATCH tensors per launch, so that describing a
+// stage needs no host-to-device copy and no staging buffer.
+constexpr int CF_TABLE_BATCH = 128;
+
+struct CfTableTensor {
+    uint64_t addr;
+    uint64_t numel;
+    uint32_t dtype;
+    uint32_t first_chunk;    // index of the tensor's first chunk in the stage's table
+};
+
+struct CfTableArgs {
+    CfTableTensor tensor[CF_TABLE_BATCH];
+    CfChunk *chunks;          // the stage's chunk table (device)
+    uint32_t *tensor_first;   // num_tensors + 1 entries (device)
+    uint32_t n;               // tensors in this launch
+    uint32_t tensor_base;     // index of tensor[0] in the stage
+    uint32_t chunk_bytes;
+    uint32_t end_chunk;       // total chunks of the stage, written behind the last tensor when `last`
+    uint32_t last;            // this launch holds the stage's last tensor
+};
+
+// Writes the chunk table entries and first-chunk indices of the tensors in `args`.
+hipError_t cf_launch_build_table(const CfTableArgs &args, hipStream_t stream);
+
+// Sets the CF_CTX_WORDS words of a context's word block to zero.
+hipError_t cf_launch_clear_words(uint32_t *words, hipStream_t stream);
+
+// words[CF_WORD_FLAGS_READ] <- words[CF_WORD_FLAGS], atomically exchanged with 0 when `clear`.
+hipError_t cf_launch_read_flags(uint32_t *words, int clear, hipStream_t stream);
+
 // First pass over `grid` workgroups, then the fixed-order second pass (one workgroup per stage).
 hipError_t cf_launch_sqnorm(const CfSqnormArgs &args, uint32_t grid, hipStream_t stream);
 
 // Per-tensor second pass over a stage's partials (after cf_launch_sqnorm on the same stream):
 // tensor t owns chunks tensor_first_chunk[t] .. tensor_first_chunk[t+1]-1.
-hipError_t cf_launch_sqnorm_tensors(const float *partials, const uint32_t *tensor_first_chunk, uint32_t num_tensors,
+hipError_t cf_launch_sqnorm_tensors(const double *partials, const uint32_t *tensor_first_chunk, uint32_t num_tensors,
                                     double *d_tensor_out, hipStream_t stream);
 
 // One workgroup per tile; a chunk holds at most 2^tile_shift tiles of CF_TILE_BYTES.
@@ -56,7 +90,8 @@ hipError_t cf_launch_blend(const CfChunk *prev, const CfChunk *next, const CfChu
                            uint32_t tile_shift, const double *d_omega_prev, const double *d_omega_next,
                            double h_omega_prev, double h_omega_next, uint32_t *words, hipStream_t stream);
 
-hipError_t cf_launch_copy(const CfChunk *src, const CfChunk *dst, uint32_t n_chunks, uint32_t tile_shift,
-                          hipStream_t stream);
+// Chunks first_chunk .. first_chunk + n_chunks - 1 of the two tables.
+hipError_t cf_launch_copy(const CfChunk *src, const CfChunk *dst, uint32_t first_chunk, uint32_t n_chunks,
+                          uint32_t tile_shift, hipStream_t stream);
 
 #endif

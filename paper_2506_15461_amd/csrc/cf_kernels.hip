@@ -49,26 +49,30 @@ constexpr uint32_t kDtypeF32 = 0u;
 // ---------------------------------------------------------------------------
 
 template <int kCtrl>
-__device__ __forceinline__ float dpp_permute(float v)
+__device__ __forceinline__ double dpp_permute(double v)
 {
-    return __int_as_float(__builtin_amdgcn_update_dpp(0, __float_as_int(v), kCtrl, 0xF, 0xF, true));
+    const int lo = __builtin_amdgcn_update_dpp(0, __double2loint(v), kCtrl, 0xF, 0xF, true);
+    const int hi = __builtin_amdgcn_update_dpp(0, __double2hiint(v), kCtrl, 0xF, 0xF, true);
+    return __hiloint2double(hi, lo);
+}
+
+__device__ __forceinline__ double read_lane(double v, int lane)
+{
+    return __hiloint2double(__builtin_amdgcn_readlane(__double2hiint(v), lane),
+                            __builtin_amdgcn_readlane(__double2loint(v), lane));
 }
 
 // Sum of v over the 64 lanes, same value in a fixed association on every run:
 // butterfly inside each row of 16 lanes (quad_perm [1,0,3,2], quad_perm
-// [2,3,0,1], row_half_mirror, row_mirror), then the four row sums as
-// (r0 + r1) + (r2 + r3).
-__device__ __forceinline__ float wave_sum(float v)
+// [2,3,0,1], row_half_mirror, row_mirror; a binary64 value moves as its two
+// halves), then the four row sums as (r0 + r1) + (r2 + r3).
+__device__ __forceinline__ double wave_sum(double v)
 {
     v += dpp_permute<0xB1>(v);
     v += dpp_permute<0x4E>(v);
     v += dpp_permute<0x141>(v);
     v += dpp_permute<0x140>(v);
-    float r0 = __int_as_float(__builtin_amdgcn_readlane(__float_as_int(v), 0));
-    float r1 = __int_as_float(__builtin_amdgcn_readlane(__float_as_int(v), 16));
-    float r2 = __int_as_float(__builtin_amdgcn_readlane(__float_as_int(v), 32));
-    float r3 = __int_as_float(__builtin_amdgcn_readlane(__float_as_int(v), 48));
-    return (r0 + r1) + (r2 + r3);
+    return (read_lane(v, 0) + read_lane(v, 16)) + (read_lane(v, 32) + read_lane(v, 48));
 }
 
 // Elements before the first 16-byte boundary at or after `addr`.
@@ -84,16 +88,24 @@ __device__ __forceinline__ uint32_t head_elems(uint64_t addr, uint32_t elem_byte
 
 // Sum of squares of this lane's share of one fp32 chunk.  Lane t of the
 // workgroup takes the 16-byte vectors t, t+256, t+512, ... of the chunk's
-// aligned body; kUnroll of them are in flight at a time.
-template <int kUnroll>
-__device__ __forceinline__ float chunk_sqsum_f32(gcf32 p, uint32_t len, uint32_t tid)
+// aligned body; kUnroll of them are in flight at a time.  Every element is
+// widened to binary64 (exact) and squared and accumulated there: one
+// conversion and one fused multiply-add per element, far below what the
+// memory stream leaves room for, so the squares of binary32 values can neither
+// underflow nor overflow and the rounding error of omega does not depend on how
+// long a lane's chain is.
+__device__ __forceinline__ void sq_acc(double &acc, float v)
 {
-    float a0 = 0.f, a1 = 0.f, a2 = 0.f, a3 = 0.f;
+    const double x = (double)v;
+    acc = __builtin_fma(x, x, acc);
+}
+
+template <int kUnroll>
+__device__ __forceinline__ double chunk_sqsum_f32(gcf32 p, uint32_t len, uint32_t tid)
+{
+    double a0 = 0.0, a1 = 0.0, a2 = 0.0, a3 = 0.0;
     const uint32_t head = head_elems((uint64_t)p, 4u, len);
-    if (tid < head) {
-        float v = p[tid];
-        a0 = __builtin_fmaf(v, v, a0);
-    }
+    if (tid < head) sq_acc(a0, p[tid]);
     gcf32x4 q = (gcf32x4)(p + head);
     const uint32_t rem = len - head;
     const uint32_t n4 = rem >> 2;
@@ -104,48 +116,41 @@ __device__ __forceinline__ float chunk_sqsum_f32(gcf32 p, uint32_t len, uint32_t
         for (int u = 0; u < kUnroll; ++u) v[u] = __builtin_nontemporal_load(q + i + u * CF_THREADS);
 #pragma unroll
         for (int u = 0; u < kUnroll; ++u) {
-            a0 = __builtin_fmaf(v[u].x, v[u].x, a0);
-            a1 = __builtin_fmaf(v[u].y, v[u].y, a1);
-            a2 = __builtin_fmaf(v[u].z, v[u].z, a2);
-            a3 = __builtin_fmaf(v[u].w, v[u].w, a3);
+            sq_acc(a0, v[u].x);
+            sq_acc(a1, v[u].y);
+            sq_acc(a2, v[u].z);
+            sq_acc(a3, v[u].w);
         }
     }
     for (; i < n4; i += CF_THREADS) {
-        f32x4 v = __builtin_nontemporal_load(q + i);
-        a0 = __builtin_fmaf(v.x, v.x, a0);
-        a1 = __builtin_fmaf(v.y, v.y, a1);
-        a2 = __builtin_fmaf(v.z, v.z, a2);
-        a3 = __builtin_fmaf(v.w, v.w, a3);
+        const f32x4 v = __builtin_nontemporal_load(q + i);
+        sq_acc(a0, v.x);
+        sq_acc(a1, v.y);
+        sq_acc(a2, v.z);
+        sq_acc(a3, v.w);
     }
     const uint32_t tail = rem & 3u;
-    if (tid < tail) {
-        float v = p[head + (n4 << 2) + tid];
-        a0 = __builtin_fmaf(v, v, a0);
-    }
+    if (tid < tail) sq_acc(a0, p[head + (n4 << 2) + tid]);
     return (a0 + a1) + (a2 + a3);
 }
 
-// The same for a bfloat16 chunk: eight elements per 16-byte vector, widened to
-// binary32 (exact), squared and accumulated in binary32.
-template <int kUnroll>
-__device__ __forceinline__ float chunk_sqsum_bf16(gcu16 p, uint32_t len, uint32_t tid)
+// The same for a bfloat16 chunk: eight elements per 16-byte vector, each
+// widened to binary32 and on to binary64 (both exact).
+__device__ __forceinline__ void sq_acc_bf16_word(double &lo_acc, double &hi_acc, uint32_t word)
 {
-    float a0 = 0.f, a1 = 0.f, a2 = 0.f, a3 = 0.f;
+    sq_acc(lo_acc, __uint_as_float(word << 16));
+    sq_acc(hi_acc, __uint_as_float(word & 0xFFFF0000u));
+}
+
+template <int kUnroll>
+__device__ __forceinline__ double chunk_sqsum_bf16(gcu16 p, uint32_t len, uint32_t tid)
+{
+    double a0 = 0.0, a1 = 0.0, a2 = 0.0, a3 = 0.0;
     const uint32_t head = head_elems((uint64_t)p, 2u, len);
-    if (tid < head) {
-        float v = __uint_as_float((uint32_t)p[tid] << 16);
-        a0 = __builtin_fmaf(v, v, a0);
-    }
+    if (tid < head) sq_acc(a0, __uint_as_float((uint32_t)p[tid] << 16));
     gcu32x4 q = (gcu32x4)(p + head);
     const uint32_t rem = len - head;
     const uint32_t n8 = rem >> 3;
-#define CF_SQ_BF16_WORD(word, lo_acc, hi_acc)                 \
-    {                                                          \
-        const float lo = __uint_as_float((word) << 16);        \
-        const float hi = __uint_as_float((word) & 0xFFFF0000u); \
-        lo_acc = __builtin_fmaf(lo, lo, lo_acc);               \
-        hi_acc = __builtin_fmaf(hi, hi, hi_acc);               \
-    }
     uint32_t i = tid;
     for (; i + (kUnroll - 1) * CF_THREADS < n8; i += kUnroll * CF_THREADS) {
         u32x4 v[kUnroll];
@@ -153,38 +158,35 @@ __device__ __forceinline__ float chunk_sqsum_bf16(gcu16 p, uint32_t len, uint32_
         for (int u = 0; u < kUnroll; ++u) v[u] = __builtin_nontemporal_load(q + i + u * CF_THREADS);
 #pragma unroll
         for (int u = 0; u < kUnroll; ++u) {
-            CF_SQ_BF16_WORD(v[u].x, a0, a1)
-            CF_SQ_BF16_WORD(v[u].y, a2, a3)
-            CF_SQ_BF16_WORD(v[u].z, a0, a1)
-            CF_SQ_BF16_WORD(v[u].w, a2, a3)
+            sq_acc_bf16_word(a0, a1, v[u].x);
+            sq_acc_bf16_word(a2, a3, v[u].y);
+            sq_acc_bf16_word(a0, a1, v[u].z);
+            sq_acc_bf16_word(a2, a3, v[u].w);
         }
     }
     for (; i < n8; i += CF_THREADS) {
         const u32x4 v = __builtin_nontemporal_load(q + i);
-        CF_SQ_BF16_WORD(v.x, a0, a1)
-        CF_SQ_BF16_WORD(v.y, a2, a3)
-        CF_SQ_BF16_WORD(v.z, a0, a1)
-        CF_SQ_BF16_WORD(v.w, a2, a3)
+        sq_acc_bf16_word(a0, a1, v.x);
+        sq_acc_bf16_word(a2, a3, v.y);
+        sq_acc_bf16_word(a0, a1, v.z);
+        sq_acc_bf16_word(a2, a3, v.w);
     }
-#undef CF_SQ_BF16_WORD
     const uint32_t tail = rem & 7u;
-    if (tid < tail) {
-        float v = __uint_as_float((uint32_t)p[head + (n8 << 3) + tid] << 16);
-        a0 = __builtin_fmaf(v, v, a0);
-    }
+    if (tid < tail) sq_acc(a0, __uint_as_float((uint32_t)p[head + (n8 << 3) + tid] << 16));
     return (a0 + a1) + (a2 + a3);
 }
 
 // First pass.  Workgroup b takes chunks b, b + grid, b + 2 grid, ... (by default
 // the grid has one workgroup per chunk).  The four wavefront sums of a chunk
-// meet in LDS and leave as ONE binary32 partial at slot `chunk` of the owning
+// meet in LDS and leave as ONE binary64 partial at slot `chunk` of the owning
 // stage's partial array, so the partials do not depend on the grid size.  There
 // is no fence and no atomic on this streaming pass: on this chip an agent-scope
 // release per workgroup (an L2 write-back) cuts a read-only stream to under
-// 40 % of what it reaches without.
+// 40 % of what it reaches without, and even a capped grid whose last-arriving
+// workgroup adds the partials up is slower than the second launch below.
 __global__ __launch_bounds__(CF_THREADS) void cf_sqnorm_partials_kernel(CfSqnormArgs args)
 {
-    __shared__ float wave_part[2][CF_WAVES];
+    __shared__ double wave_part[2][CF_WAVES];
     const uint32_t tid = threadIdx.x;
     const uint32_t wave = tid >> 6;
     const uint32_t lane = tid & 63u;
@@ -195,9 +197,9 @@ __global__ __launch_bounds__(CF_THREADS) void cf_sqnorm_partials_kernel(CfSqnorm
         while (s + 1 < args.n_seg && c >= args.seg[s + 1].chunk_begin) ++s;
         const uint32_t local = c - args.seg[s].chunk_begin;
         const CfChunk ch = args.seg[s].chunks[local];
-        float t = (ch.dtype == kDtypeF32) ? chunk_sqsum_f32<8>((gcf32)ch.addr, ch.len, tid)
-                                          : chunk_sqsum_bf16<8>((gcu16)ch.addr, ch.len, tid);
-        float w = wave_sum(t);
+        const double t = (ch.dtype == kDtypeF32) ? chunk_sqsum_f32<8>((gcf32)ch.addr, ch.len, tid)
+                                                 : chunk_sqsum_bf16<8>((gcu16)ch.addr, ch.len, tid);
+        const double w = wave_sum(t);
         // Two LDS rows used alternately: one barrier per chunk is enough, because a
         // row is rewritten only after the barrier of the chunk in between.
         if (lane == 0) wave_part[parity][wave] = w;
@@ -217,10 +219,10 @@ __global__ __launch_bounds__(CF_FINALIZE_THREADS) void cf_sqnorm_finalize_kernel
     __shared__ double red[CF_FINALIZE_THREADS];
     const uint32_t tid = threadIdx.x;
     const uint32_t k = blockIdx.x;
-    const float *part = args.seg[k].partials;
+    const double *part = args.seg[k].partials;
     const uint64_t np = args.seg[k].n_chunks;
     double acc = 0.0;
-    for (uint64_t i = tid; i < np; i += CF_FINALIZE_THREADS) acc += (double)part[i];
+    for (uint64_t i = tid; i < np; i += CF_FINALIZE_THREADS) acc += part[i];
     red[tid] = acc;
     __syncthreads();
     for (uint32_t off = CF_FINALIZE_THREADS / 2; off > 0; off >>= 1) {
@@ -236,7 +238,7 @@ __global__ __launch_bounds__(CF_FINALIZE_THREADS) void cf_sqnorm_finalize_kernel
 
 // Second pass, per tensor: workgroup t adds the partials of the chunks of tensor
 // t (chunks first[t] .. first[t+1]-1 of the stage) in binary64 in a fixed order.
-__global__ __launch_bounds__(CF_THREADS) void cf_sqnorm_finalize_tensors_kernel(const float *partials,
+__global__ __launch_bounds__(CF_THREADS) void cf_sqnorm_finalize_tensors_kernel(const double *partials,
                                                                                const uint32_t *first,
                                                                                double *tensor_out)
 {
@@ -245,7 +247,7 @@ __global__ __launch_bounds__(CF_THREADS) void cf_sqnorm_finalize_tensors_kernel(
     const uint32_t lo = first[blockIdx.x];
     const uint32_t hi = first[blockIdx.x + 1];
     double acc = 0.0;
-    for (uint32_t i = lo + tid; i < hi; i += CF_THREADS) acc += (double)partials[i];
+    for (uint32_t i = lo + tid; i < hi; i += CF_THREADS) acc += partials[i];
     red[tid] = acc;
     __syncthreads();
     for (uint32_t off = CF_THREADS / 2; off > 0; off >>= 1) {
@@ -428,7 +430,14 @@ __global__ __launch_bounds__(CF_TILE_THREADS) void cf_blend_kernel(const CfChunk
         den = 2.0;
         if (blockIdx.x == 0 && tid == 0) atomicOr(&words[CF_WORD_FLAGS], kFlagDegenerateOmega);
     }
-    w.rcp = 1.0 / den;
+    // The equation does not change when both weights are multiplied by one
+    // number: scale them by the power of two that brings their sum into [1, 2)
+    // (exact), so that no product weight x value leaves the binary64 range
+    // whatever the magnitude of the omegas.
+    const int scale = 1023 - (int)((uint64_t)__double_as_longlong(den) >> 52);
+    w.wp = __builtin_ldexp(w.wp, scale);
+    w.wn = __builtin_ldexp(w.wn, scale);
+    w.rcp = 1.0 / (w.wp + w.wn);
 
     if (co.dtype == kDtypeF32)
         blend_tile_f32(w, (gcf32)ca.addr, (gcf32)cb.addr, (gf32)co.addr, co.len, tile, tid);
@@ -441,10 +450,10 @@ __global__ __launch_bounds__(CF_TILE_THREADS) void cf_blend_kernel(const CfChunk
 // ---------------------------------------------------------------------------
 
 __global__ __launch_bounds__(CF_TILE_THREADS) void cf_copy_kernel(const CfChunk *src, const CfChunk *dst,
-                                                             uint32_t tile_shift)
+                                                             uint32_t first_chunk, uint32_t tile_shift)
 {
     const uint32_t tid = threadIdx.x;
-    const uint32_t c = blockIdx.x >> tile_shift;
+    const uint32_t c = first_chunk + (blockIdx.x >> tile_shift);
     const uint32_t tile = blockIdx.x & ((1u << tile_shift) - 1u);
     const CfChunk cd = dst[c];
     const uint32_t esize = (cd.dtype == kDtypeF32) ? 4u : 2u;
@@ -487,6 +496,46 @@ __global__ __launch_bounds__(CF_TILE_THREADS) void cf_copy_kernel(const CfChunk 
     }
 }
 
+// ---------------------------------------------------------------------------
+// Set-up kernels: nothing here touches tensor data.
+// ---------------------------------------------------------------------------
+
+// Workgroup b writes the chunk table entries of tensor b of the launch, whose
+// description arrived in the kernel argument block: a stage is described to
+// the device without a host-to-device copy, asynchronously on the caller's
+// stream.
+__global__ __launch_bounds__(CF_THREADS) void cf_build_table_kernel(CfTableArgs args)
+{
+    const uint32_t b = blockIdx.x;
+    const CfTableTensor t = args.tensor[b];
+    const uint32_t esize = (t.dtype == kDtypeF32) ? 4u : 2u;
+    const uint64_t chunk_elems = args.chunk_bytes / esize;
+    const uint64_t n = (t.numel + chunk_elems - 1) / chunk_elems;
+    for (uint64_t j = threadIdx.x; j < n; j += CF_THREADS) {
+        const uint64_t first = j * chunk_elems;
+        const uint64_t left = t.numel - first;
+        CfChunk c;
+        c.addr = t.addr + first * esize;
+        c.len = (uint32_t)(left < chunk_elems ? left : chunk_elems);
+        c.dtype = t.dtype;
+        args.chunks[t.first_chunk + j] = c;
+    }
+    if (threadIdx.x == 0) {
+        args.tensor_first[args.tensor_base + b] = t.first_chunk;
+        if (args.last && b + 1 == args.n) args.tensor_first[args.tensor_base + args.n] = args.end_chunk;
+    }
+}
+
+__global__ __launch_bounds__(CF_CTX_WORDS) void cf_clear_words_kernel(uint32_t *words) { words[threadIdx.x] = 0u; }
+
+// The sticky flags are read, and cleared if asked, in one atomic step, so a
+// flag raised by a kernel on another stream is either seen by this read or
+// still there for the next.
+__global__ __launch_bounds__(64) void cf_read_flags_kernel(uint32_t *words, int clear)
+{
+    words[CF_WORD_FLAGS_READ] = clear ? atomicExch(&words[CF_WORD_FLAGS], 0u) : atomicOr(&words[CF_WORD_FLAGS], 0u);
+}
+
 }  // namespace
 
 hipError_t cf_launch_sqnorm(const CfSqnormArgs &args, uint32_t grid, hipStream_t stream)
@@ -500,7 +549,7 @@ hipError_t cf_launch_sqnorm(const CfSqnormArgs &args, uint32_t grid, hipStream_t
     return hipGetLastError();
 }
 
-hipError_t cf_launch_sqnorm_tensors(const float *partials, const uint32_t *tensor_first_chunk, uint32_t num_tensors,
+hipError_t cf_launch_sqnorm_tensors(const double *partials, const uint32_t *tensor_first_chunk, uint32_t num_tensors,
                                     double *d_tensor_out, hipStream_t stream)
 {
     hipLaunchKernelGGL(cf_sqnorm_finalize_tensors_kernel, dim3(num_tensors), dim3(CF_THREADS), 0, stream, partials,
@@ -517,10 +566,28 @@ hipError_t cf_launch_blend(const CfChunk *prev, const CfChunk *next, const CfChu
     return hipGetLastError();
 }
 
-hipError_t cf_launch_copy(const CfChunk *src, const CfChunk *dst, uint32_t n_chunks, uint32_t tile_shift,
-                          hipStream_t stream)
+hipError_t cf_launch_copy(const CfChunk *src, const CfChunk *dst, uint32_t first_chunk, uint32_t n_chunks,
+                          uint32_t tile_shift, hipStream_t stream)
 {
     hipLaunchKernelGGL(cf_copy_kernel, dim3(n_chunks << tile_shift), dim3(CF_TILE_THREADS), 0, stream, src, dst,
-                       tile_shift);
+                       first_chunk, tile_shift);
+    return hipGetLastError();
+}
+
+hipError_t cf_launch_build_table(const CfTableArgs &args, hipStream_t stream)
+{
+    hipLaunchKernelGGL(cf_build_table_kernel, dim3(args.n), dim3(CF_THREADS), 0, stream, args);
+    return hipGetLastError();
+}
+
+hipError_t cf_launch_clear_words(uint32_t *words, hipStream_t stream)
+{
+    hipLaunchKernelGGL(cf_clear_words_kernel, dim3(1), dim3(CF_CTX_WORDS), 0, stream, words);
+    return hipGetLastError();
+}
+
+hipError_t cf_launch_read_flags(uint32_t *words, int clear, hipStream_t stream)
+{
+    hipLaunchKernelGGL(cf_read_flags_kernel, dim3(1), dim3(1), 0, stream, words, clear);
     return hipGetLastError();
 }

@@ -40,6 +40,9 @@ static int host_only(void)
     d[1].data = (void *)0x1004;
     CHECK(cf_check_stage_pair(&d[0], 1, &d[1], 1) == CF_ERR_ALIAS);
     CHECK(cf_ctx_create(0, NULL, NULL) == CF_ERR_NULL);
+    CHECK(cf_workspace_bytes() >= 8);
+    CHECK(cf_stage_table_bytes(NULL, d, 1) == UINT64_MAX);
+    CHECK(cf_ctx_create_in(0, NULL, NULL, 256, NULL, NULL) == CF_ERR_NULL);
     return 0;
 }
 
@@ -51,6 +54,9 @@ static int device_path(void)
     float *d_a, *d_b, *d_o, *d_g;
     double *d_omega, omega[2];
     cf_ctx *ctx = NULL;
+    void *d_ws = NULL, *d_tab_a = NULL, *d_tab_g = NULL;
+    uint64_t tab_bytes;
+    hipStream_t stream;
     cf_stage *sa = NULL, *sb = NULL, *so = NULL, *sg = NULL;
     const cf_stage *grads[2];
     cf_tensor t;
@@ -68,13 +74,23 @@ static int device_path(void)
     CHECK(hipMemcpy(d_g, h, n * 4, hipMemcpyHostToDevice) == hipSuccess);
     CHECK(hipMemset(d_o, 0xFF, n * 4) == hipSuccess);
 
-    CHECK(cf_ctx_create(0, NULL, &ctx) == CF_OK);
+    /* the context and two of the stages in memory this program allocates, set up on its own
+     * stream without a wait; the other two stages through the allocating convenience calls */
+    CHECK(hipStreamCreateWithFlags(&stream, hipStreamNonBlocking) == hipSuccess);
+    CHECK(hipMalloc(&d_ws, cf_workspace_bytes()) == hipSuccess);
+    CHECK(cf_ctx_create_in(0, NULL, d_ws, cf_workspace_bytes(), stream, &ctx) == CF_OK);
     memset(&t, 0, sizeof t);
     t.numel = n; t.dtype = CF_F32;
-    t.data = d_a; CHECK(cf_stage_create(ctx, &t, 1, &sa) == CF_OK);
+    t.data = d_a;
+    tab_bytes = cf_stage_table_bytes(ctx, &t, 1);
+    CHECK(tab_bytes != UINT64_MAX && tab_bytes > 0);
+    CHECK(hipMalloc(&d_tab_a, tab_bytes) == hipSuccess && hipMalloc(&d_tab_g, tab_bytes) == hipSuccess);
+    CHECK(cf_stage_create_in(ctx, &t, 1, d_tab_a, tab_bytes - 1, stream, &sa) == CF_ERR_LIMIT);
+    CHECK(cf_stage_create_in(ctx, &t, 1, d_tab_a, tab_bytes, stream, &sa) == CF_OK);
+    t.data = d_g; CHECK(cf_stage_create_in(ctx, &t, 1, d_tab_g, tab_bytes, stream, &sg) == CF_OK);
+    CHECK(hipStreamSynchronize(stream) == hipSuccess);     /* the calls below use the default stream */
     t.data = d_b; CHECK(cf_stage_create(ctx, &t, 1, &sb) == CF_OK);
     t.data = d_o; CHECK(cf_stage_create(ctx, &t, 1, &so) == CF_OK);
-    t.data = d_g; CHECK(cf_stage_create(ctx, &t, 1, &sg) == CF_OK);
     CHECK(cf_stage_numel(sa) == n && cf_stage_nbytes(sa) == 4 * n && cf_stage_num_tensors(sa) == 1);
 
     /* omega of the constant gradient, and of the (constant) stage b used as a second "gradient" */
@@ -99,12 +115,24 @@ static int device_path(void)
     CHECK(cf_copy_stage(ctx, sg, so, NULL) == CF_OK);
     CHECK(hipMemcpy(h, d_o, n * 4, hipMemcpyDeviceToHost) == hipSuccess);
     for (k = 0; k < n; ++k) CHECK(h[k] == cg);
+    /* a replica refresh in two slices */
+    CHECK(hipMemset(d_o, 0, n * 4) == hipSuccess);
+    CHECK(cf_stage_num_chunks(so) == 10);                   /* 300007 floats in chunks of 32768 */
+    CHECK(cf_copy_stage_range(ctx, sa, so, 0, 4, NULL) == CF_OK);
+    CHECK(hipMemcpy(h, d_o, n * 4, hipMemcpyDeviceToHost) == hipSuccess);
+    for (k = 0; k < n; ++k) CHECK(h[k] == (k < 4 * 32768 ? ca : 0.0f));
+    CHECK(cf_copy_stage_range(ctx, sa, so, 4, 6, NULL) == CF_OK);
+    CHECK(hipMemcpy(h, d_o, n * 4, hipMemcpyDeviceToHost) == hipSuccess);
+    for (k = 0; k < n; ++k) CHECK(h[k] == ca);
+    CHECK(cf_copy_stage_range(ctx, sa, so, 9, 2, NULL) == CF_ERR_LIMIT);
     CHECK(cf_read_flags(ctx, NULL, &flags, 0) == CF_OK && flags == 0);
     /* errors */
     CHECK(cf_ctx_destroy(ctx) == CF_ERR_CONTEXT);    /* stages alive */
     CHECK(cf_stage_destroy(sa) == CF_OK && cf_stage_destroy(sb) == CF_OK);
     CHECK(cf_stage_destroy(so) == CF_OK && cf_stage_destroy(sg) == CF_OK);
     CHECK(cf_ctx_destroy(ctx) == CF_OK);
+    CHECK(hipStreamDestroy(stream) == hipSuccess);
+    hipFree(d_ws); hipFree(d_tab_a); hipFree(d_tab_g);
     hipFree(d_a); hipFree(d_b); hipFree(d_o); hipFree(d_g); hipFree(d_omega);
     free(h);
     return 0;
