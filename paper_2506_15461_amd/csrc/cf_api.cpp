@@ -221,6 +221,39 @@ void forget_stage(cf_ctx *ctx, uint64_t id)
             v.end());
 }
 
+// Enqueues the kernels that write a stage's chunk table and first-chunk indices.  The tensor
+// list travels to the device in kernel argument blocks, CF_TABLE_BATCH tensors at a time: nothing
+// is copied and nothing is waited for.
+hipError_t enqueue_table(const cf_ctx *ctx, const cf_tensor *tensors, uint32_t num_tensors, CfChunk *d_chunks,
+                         uint32_t *d_tensor_first, uint64_t n_chunks, hipStream_t stream)
+{
+    const uint32_t chunk_bytes = ctx->tuning.chunk_bytes;
+    CfTableArgs args;
+    std::memset(&args, 0, sizeof args);
+    args.chunks = d_chunks;
+    args.tensor_first = d_tensor_first;
+    args.chunk_bytes = chunk_bytes;
+    args.end_chunk = (uint32_t)n_chunks;
+    uint64_t first_chunk = 0;
+    for (uint32_t t = 0; t < num_tensors; ++t) {
+        const cf_tensor &d = tensors[t];
+        CfTableTensor &slot = args.tensor[args.n++];
+        slot.addr = reinterpret_cast<uint64_t>(d.data);
+        slot.numel = d.numel;
+        slot.dtype = (uint32_t)d.dtype;
+        slot.first_chunk = (uint32_t)first_chunk;
+        first_chunk += chunks_of(d.numel, chunk_bytes / elem_size(d.dtype));
+        if (args.n == CF_TABLE_BATCH || t + 1 == num_tensors) {
+            args.last = (t + 1 == num_tensors);
+            hipError_t e = cf_launch_build_table(args, stream);
+            if (e != hipSuccess) return e;
+            args.tensor_base += args.n;
+            args.n = 0;
+        }
+    }
+    return hipSuccess;
+}
+
 uint32_t sqnorm_grid(const cf_ctx *ctx, uint32_t n_chunks)
 {
     uint64_t g = n_chunks;
@@ -432,41 +465,17 @@ cf_status cf_stage_create_in(cf_ctx *ctx, const cf_tensor *tensors, uint32_t num
         stage->d_tensor_first = reinterpret_cast<uint32_t *>(base + layout.first_off);
         stage->d_partials = reinterpret_cast<double *>(base + layout.partials_off);
     }
-    // The tensor list travels to the device in kernel argument blocks, CF_TABLE_BATCH tensors at a
-    // time; the kernel writes the chunk table.  Nothing is copied and nothing is waited for.
-    const uint32_t chunk_bytes = ctx->tuning.chunk_bytes;
-    DeviceGuard guard(ctx->device);
-    if (!guard.ok()) {
-        delete stage;
-        return CF_ERR_HIP;
-    }
-    CfTableArgs args;
-    std::memset(&args, 0, sizeof args);
-    args.chunks = stage->d_chunks;
-    args.tensor_first = stage->d_tensor_first;
-    args.chunk_bytes = chunk_bytes;
-    args.end_chunk = (uint32_t)n_chunks;
-    uint64_t first_chunk = 0;
     for (uint32_t t = 0; t < num_tensors; ++t) {
         const cf_tensor &d = tensors[t];
         stage->tensors.push_back({reinterpret_cast<uint64_t>(d.data), d.numel, d.dtype});
         stage->numel += d.numel;
         stage->nbytes += d.numel * elem_size(d.dtype);
-        CfTableTensor &slot = args.tensor[args.n++];
-        slot.addr = reinterpret_cast<uint64_t>(d.data);
-        slot.numel = d.numel;
-        slot.dtype = (uint32_t)d.dtype;
-        slot.first_chunk = (uint32_t)first_chunk;
-        first_chunk += chunks_of(d.numel, chunk_bytes / elem_size(d.dtype));
-        if (args.n == CF_TABLE_BATCH || t + 1 == num_tensors) {
-            args.last = (t + 1 == num_tensors);
-            if (cf_launch_build_table(args, static_cast<hipStream_t>(stream)) != hipSuccess) {
-                delete stage;
-                return CF_ERR_HIP;
-            }
-            args.tensor_base += args.n;
-            args.n = 0;
-        }
+    }
+    DeviceGuard guard(ctx->device);
+    if (!guard.ok() || enqueue_table(ctx, tensors, num_tensors, stage->d_chunks, stage->d_tensor_first, n_chunks,
+                                     static_cast<hipStream_t>(stream)) != hipSuccess) {
+        delete stage;
+        return CF_ERR_HIP;
     }
     ctx->live_stages.fetch_add(1);
     *out = stage;
