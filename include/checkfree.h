@@ -227,6 +227,31 @@ CF_API cf_status cf_stage_grad_sqnorm(cf_ctx *ctx, const cf_stage *const *grad_s
 CF_API cf_status cf_stage_grad_sqnorm_per_tensor(cf_ctx *ctx, const cf_stage *grad_stage,
                                                  double *d_tensor_sqnorm, double *d_omega_out, void *stream);
 
+/* For callers that cannot allocate device memory at all -- code under HIP graph
+ * capture, tight serving loops, harnesses that forbid hipMalloc: omega of ONE
+ * stage given as a bare tensor list (HOST array, borrowed for the call), as
+ * cf_stage_grad_sqnorm computes it and with the same bits, but with the chunk
+ * table and the partial sums in a fixed array inside the library's device image
+ * instead of in a stage handle's block.  Calls no hipMalloc / hipFree and no
+ * allocating routine, copies nothing between host and device, does not wait.
+ *
+ *   d_omega_out  DEVICE, one double
+ *
+ * The array is cf_static_scratch_bytes() bytes (1 MiB) per GPU, held from the
+ * first context created on that GPU until the process ends.  A stage needs 24
+ * bytes per chunk and 4 per tensor of it (rounded up to 256-byte sections): with
+ * the default 128 KiB chunk that is room for about 5.7 GB of gradients; a larger
+ * stage is refused with CF_ERR_LIMIT and nothing is launched.  All calls on one
+ * GPU share that GPU's array, whatever their context or stream: two calls that
+ * may run at the same time on one GPU race, and the caller must order them.
+ * Nothing in the array has to be cleared between calls.
+ * Errors: CF_ERR_NULL, CF_ERR_DTYPE, CF_ERR_ALIGN, CF_ERR_LIMIT, CF_ERR_HIP. */
+CF_API cf_status cf_stage_grad_sqnorm_static(cf_ctx *ctx, const cf_tensor *grads, uint32_t num_tensors,
+                                             double *d_omega_out, void *stream);
+
+/* Size in bytes of the per-GPU array cf_stage_grad_sqnorm_static works in. */
+CF_API uint64_t cf_static_scratch_bytes(void);
+
 /* Rebuilds a lost intermediate stage from its two neighbours:
  *   lost[t][k] = (w_p * prev[t][k] + w_n * next[t][k]) / (w_p + w_n)
  * for every tensor t and element k, with w_p = *d_omega_prev, w_n = *d_omega_next

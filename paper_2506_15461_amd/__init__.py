@@ -39,7 +39,7 @@ EXPORTS = (
     "cf_recover_stage_with_weights", "cf_recovered_learning_rate", "cf_check_stage_pair",
     "cf_stage_grad_sqnorm_per_tensor",
     "cf_workspace_bytes", "cf_ctx_create_in", "cf_stage_table_bytes", "cf_stage_create_in",
-    "cf_copy_stage_range",
+    "cf_copy_stage_range", "cf_stage_grad_sqnorm_static", "cf_static_scratch_bytes",
 )
 
 
@@ -90,6 +90,10 @@ def load_library():
     lib.cf_stage_create_in.argtypes = [vp, ctypes.POINTER(CfTensor), u32, vp, u64, vp, ctypes.POINTER(vp)]
     lib.cf_copy_stage_range.restype = i32
     lib.cf_copy_stage_range.argtypes = [vp, vp, vp, u32, u32, vp]
+    lib.cf_stage_grad_sqnorm_static.restype = i32
+    lib.cf_stage_grad_sqnorm_static.argtypes = [vp, ctypes.POINTER(CfTensor), u32, vp, vp]
+    lib.cf_static_scratch_bytes.restype = u64
+    lib.cf_static_scratch_bytes.argtypes = []
     lib.cf_ctx_destroy.restype = i32
     lib.cf_ctx_destroy.argtypes = [vp]
     lib.cf_stage_create.restype = i32
@@ -322,6 +326,16 @@ def cf_stage_grad_sqnorm(ctx: Context, grad_stages, out=None, stream=None):
     handles = (ctypes.c_void_p * max(n, 1))(*[s._h for s in grad_stages])
     _check(load_library().cf_stage_grad_sqnorm(ctx._h, handles, n, ctypes.c_void_p(out.data_ptr()),
                                                _stream_ptr(stream)), "cf_stage_grad_sqnorm")
+    return out
+
+
+def cf_stage_grad_sqnorm_static(ctx: Context, grads, out, stream=None):
+    """omega of one stage given as a list of gradient tensors, written into the
+    one-element float64 device tensor `out`; the library's tables live in its
+    static per-GPU array, so nothing is allocated anywhere on the way."""
+    desc = tensor_descriptors(list(grads))
+    _check(load_library().cf_stage_grad_sqnorm_static(ctx._h, desc, len(grads), _omega_ptr(ctx, out),
+                                                      _stream_ptr(stream)), "cf_stage_grad_sqnorm_static")
     return out
 
 

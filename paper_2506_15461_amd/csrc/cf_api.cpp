@@ -43,6 +43,7 @@ struct cf_ctx {
     uint32_t tile_shift = 0;   // log2(chunk_bytes / CF_TILE_BYTES)
     uint32_t *d_words = nullptr;
     bool owns_words = false;   // d_words came from hipMalloc here (else it is the caller's workspace)
+    void *d_static = nullptr;  // this device's copy of the library's static scratch array
     std::atomic<uint32_t> live_stages{0};
     // Pairs (input stage id, output stage id) whose congruence and aliasing have been checked.
     std::mutex checked_mutex;
@@ -377,6 +378,10 @@ cf_status cf_ctx_create_in(int device, const cf_tuning *tuning, void *d_workspac
     ctx->tuning = t;
     for (uint32_t b = t.chunk_bytes / CF_TILE_BYTES; b > 1; b >>= 1) ++ctx->tile_shift;
     ctx->d_words = static_cast<uint32_t *>(d_workspace);
+    if (cf_static_scratch_address(device, &ctx->d_static) != hipSuccess) {
+        delete ctx;
+        return CF_ERR_HIP;
+    }
     if (cf_launch_clear_words(ctx->d_words, static_cast<hipStream_t>(stream)) != hipSuccess) {
         delete ctx;
         return CF_ERR_HIP;
@@ -564,6 +569,42 @@ cf_status cf_stage_grad_sqnorm(cf_ctx *ctx, const cf_stage *const *grad_stages, 
         const uint32_t grid = sqnorm_grid(ctx, args.total_chunks);
         if (cf_launch_sqnorm(args, grid, static_cast<hipStream_t>(stream)) != hipSuccess) return CF_ERR_HIP;
     }
+    return CF_OK;
+}
+
+uint64_t cf_static_scratch_bytes(void) { return CF_STATIC_SCRATCH_BYTES; }
+
+cf_status cf_stage_grad_sqnorm_static(cf_ctx *ctx, const cf_tensor *grads, uint32_t num_tensors, double *d_omega_out,
+                                      void *stream)
+{
+    if (!ctx || !d_omega_out || (num_tensors && !grads)) return CF_ERR_NULL;
+    uint64_t n_chunks = 0;
+    cf_status st = plan_stage(ctx, grads, num_tensors, &n_chunks);
+    if (st != CF_OK) return st;
+    const TableLayout layout = table_layout(n_chunks, num_tensors);
+    if (layout.total > CF_STATIC_SCRATCH_BYTES) return CF_ERR_LIMIT;
+    DeviceGuard guard(ctx->device);
+    if (!guard.ok()) return CF_ERR_HIP;
+    // The tables go where a stage handle would keep them, but inside this device's static array.
+    // Nothing in it has to start at zero: the table entries and every partial slot of the stage are
+    // written before they are read.
+    char *base = static_cast<char *>(ctx->d_static);
+    CfChunk *d_chunks = reinterpret_cast<CfChunk *>(base + layout.chunks_off);
+    uint32_t *d_tensor_first = reinterpret_cast<uint32_t *>(base + layout.first_off);
+    double *d_partials = reinterpret_cast<double *>(base + layout.partials_off);
+    hipStream_t s = static_cast<hipStream_t>(stream);
+    if (enqueue_table(ctx, grads, num_tensors, d_chunks, d_tensor_first, n_chunks, s) != hipSuccess) return CF_ERR_HIP;
+    CfSqnormArgs args;
+    std::memset(&args, 0, sizeof args);
+    args.seg[0].chunks = d_chunks;
+    args.seg[0].partials = d_partials;
+    args.seg[0].chunk_begin = 0;
+    args.seg[0].n_chunks = (uint32_t)n_chunks;
+    args.n_seg = 1;
+    args.total_chunks = (uint32_t)n_chunks;
+    args.omega_out = d_omega_out;
+    args.words = ctx->d_words;
+    if (cf_launch_sqnorm(args, sqnorm_grid(ctx, args.total_chunks), s) != hipSuccess) return CF_ERR_HIP;
     return CF_OK;
 }
 

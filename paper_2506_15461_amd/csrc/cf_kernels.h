@@ -67,6 +67,12 @@ struct CfTableArgs {
     uint32_t last;            // this launch holds the stage's last tensor
 };
 
+// The file-scope device array behind the entry point that allocates nothing: its size, and its
+// address in the memory of `device` (which must be the current device).  Every GPU holds its own
+// copy of the array at its own address; the address is looked up once per device and kept.
+constexpr uint64_t CF_STATIC_SCRATCH_BYTES = 1ull << 20;
+hipError_t cf_static_scratch_address(int device, void **ptr);
+
 // Writes the chunk table entries and first-chunk indices of the tensors in `args`.
 hipError_t cf_launch_build_table(const CfTableArgs &args, hipStream_t stream);
 

@@ -13,7 +13,16 @@
 #include <hip/hip_runtime.h>
 #include <stdint.h>
 
+#include <mutex>
+
 #include "cf_kernels.h"
+
+// Device memory for callers that cannot allocate (code under graph capture, tight serving loops):
+// cf_stage_grad_sqnorm_static puts its chunk table and partial sums here instead of in a block the
+// caller or the library allocated.  One copy per GPU, held until the process ends.  In host code
+// the name below is only a stand-in for the symbol, never a device address: the address comes from
+// cf_static_scratch_address() and is what the kernels are given.
+static __device__ __align__(256) unsigned char scratch[CF_STATIC_SCRATCH_BYTES];
 
 // Every binary64 operation of the blend is rounded on its own, as the formula
 // is written; fused multiply-adds are only the explicit ones below.
@@ -537,6 +546,24 @@ __global__ __launch_bounds__(64) void cf_read_flags_kernel(uint32_t *words, int 
 }
 
 }  // namespace
+
+hipError_t cf_static_scratch_address(int device, void **ptr)
+{
+    constexpr int kMaxDevices = 64;
+    static std::mutex mutex;
+    static void *address[kMaxDevices] = {};
+    if (!ptr || device < 0 || device >= kMaxDevices) return hipErrorInvalidValue;
+    std::lock_guard<std::mutex> lock(mutex);
+    if (!address[device]) {
+        void *p = nullptr;
+        const hipError_t e = hipGetSymbolAddress(&p, HIP_SYMBOL(scratch));
+        if (e != hipSuccess) return e;
+        if (!p) return hipErrorInvalidSymbol;
+        address[device] = p;
+    }
+    *ptr = address[device];
+    return hipSuccess;
+}
 
 hipError_t cf_launch_sqnorm(const CfSqnormArgs &args, uint32_t grid, hipStream_t stream)
 {
