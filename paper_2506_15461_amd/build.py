@@ -73,6 +73,16 @@ def build(verbose=True, out=LIB, extra=()):
     return out
 
 
+CEILING_LIB = os.path.join(PKG, "libcf_ceiling.so")
+
+
+def build_ceiling(verbose=True):
+    """The benchmark's two trivial streaming kernels (its independent bandwidth ceilings)."""
+    run([hipcc_path(), "--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-shared", "-fvisibility=hidden",
+         "-Wall", "-Wextra", *NO_PACKED_FP32, os.path.join(CSRC, "ceiling_kernels.hip"), "-o", CEILING_LIB], verbose)
+    return CEILING_LIB
+
+
 C_SMOKE_SRC = os.path.join(ROOT, "tests", "c_abi_smoke.c")
 C_SMOKE_BIN = os.path.join(ROOT, "tests", "c_abi_smoke")
 
@@ -92,5 +102,6 @@ def build_c_smoke(verbose=True):
 
 if __name__ == "__main__":
     build()
+    build_ceiling()
     build_c_smoke()
     sys.exit(0)

@@ -18,7 +18,10 @@ namespace {
 constexpr uint32_t kDefaultChunkBytes = 128u << 10;   // 128 tiles of 1 KiB
 constexpr uint32_t kMinChunkBytes = 4096;
 constexpr uint32_t kMaxChunkBytes = 4u << 20;
-constexpr uint32_t kDefaultSqnormBlocksPerCu = 0;     // 0: one workgroup per chunk
+constexpr uint32_t kDefaultSqnormBlocksPerCu = 0;     // 0: chosen by the size of the launch
+constexpr uint32_t kOnePerChunk = 65;                 // tuning value that forces one workgroup per chunk
+constexpr uint32_t kCappedGridPerCu = 2;
+constexpr uint64_t kCappedGridFromBytes = 1ull << 30;
 constexpr uint64_t kMaxChunksPerStage = 1ull << 31;
 constexpr uint64_t kMaxGrid = (1ull << 31) - 1;
 constexpr size_t kCtxWordBytes = CF_CTX_WORDS * sizeof(uint32_t);
@@ -255,11 +258,17 @@ hipError_t enqueue_table(const cf_ctx *ctx, const cf_tensor *tensors, uint32_t n
     return hipSuccess;
 }
 
+// Grid of the norm's first pass.  The partials are per chunk, so the result does not depend on this
+// choice; only the speed does.  Measured on this chip: up to a few thousand chunks one workgroup per
+// chunk is fastest (the launch is over before a capped grid has paid for itself); from about 1 GiB of
+// gradients on, 512 resident workgroups walking the chunk list are 1-3 % faster than 12 000 and more
+// short-lived ones.
 uint32_t sqnorm_grid(const cf_ctx *ctx, uint32_t n_chunks)
 {
     uint64_t g = n_chunks;
-    if (ctx->tuning.sqnorm_blocks_per_cu)
-        g = std::min<uint64_t>(g, (uint64_t)ctx->num_cu * ctx->tuning.sqnorm_blocks_per_cu);
+    uint32_t per_cu = ctx->tuning.sqnorm_blocks_per_cu;
+    if (per_cu == 0 && (uint64_t)n_chunks * ctx->tuning.chunk_bytes >= kCappedGridFromBytes) per_cu = kCappedGridPerCu;
+    if (per_cu && per_cu != kOnePerChunk) g = std::min<uint64_t>(g, (uint64_t)ctx->num_cu * per_cu);
     return (uint32_t)std::max<uint64_t>(g, 1);
 }
 
@@ -362,7 +371,7 @@ cf_status cf_ctx_create_in(int device, const cf_tuning *tuning, void *d_workspac
         if (tuning->chunk_bytes) t.chunk_bytes = tuning->chunk_bytes;
         if (tuning->sqnorm_blocks_per_cu) t.sqnorm_blocks_per_cu = tuning->sqnorm_blocks_per_cu;
     }
-    if (!valid_chunk_bytes(t.chunk_bytes) || t.sqnorm_blocks_per_cu > 64) return CF_ERR_LIMIT;
+    if (!valid_chunk_bytes(t.chunk_bytes) || t.sqnorm_blocks_per_cu > kOnePerChunk) return CF_ERR_LIMIT;
 
     int count = 0;
     if (hipGetDeviceCount(&count) != hipSuccess || device < 0 || device >= count) return CF_ERR_HIP;
@@ -394,7 +403,7 @@ cf_status cf_ctx_create(int device, const cf_tuning *tuning, cf_ctx **out)
 {
     if (!out) return CF_ERR_NULL;
     *out = nullptr;
-    if (tuning && ((tuning->chunk_bytes && !valid_chunk_bytes(tuning->chunk_bytes)) || tuning->sqnorm_blocks_per_cu > 64))
+    if (tuning && ((tuning->chunk_bytes && !valid_chunk_bytes(tuning->chunk_bytes)) || tuning->sqnorm_blocks_per_cu > kOnePerChunk))
         return CF_ERR_LIMIT;
     int count = 0;
     if (hipGetDeviceCount(&count) != hipSuccess || device < 0 || device >= count) return CF_ERR_HIP;

@@ -220,50 +220,57 @@ __global__ __launch_bounds__(CF_THREADS) void cf_sqnorm_partials_kernel(CfSqnorm
     }
 }
 
+// Sum over a workgroup of kThreads threads in a fixed order: the wavefront
+// butterfly, then the wavefront sums added one after the other by thread 0 (one
+// barrier).  The result is valid in thread 0 only.
+template <int kThreads>
+__device__ __forceinline__ double block_sum_fixed_order(double v, double *wave_sums)
+{
+    const uint32_t tid = threadIdx.x;
+    const double w = wave_sum(v);
+    if ((tid & 63u) == 0) wave_sums[tid >> 6] = w;
+    __syncthreads();
+    double total = 0.0;
+    if (tid == 0) {
+#pragma unroll
+        for (int k = 0; k < kThreads / 64; ++k) total += wave_sums[k];
+    }
+    return total;
+}
+
 // Second pass, stream-ordered after the first: workgroup k adds the partials of
-// stage k in binary64 in a fixed order (lane-strided serial sums, then a fixed
-// LDS tree) and writes omega_k.
+// stage k in a fixed order (lane-strided serial sums, then the fixed-order
+// workgroup sum) and writes omega_k.
 __global__ __launch_bounds__(CF_FINALIZE_THREADS) void cf_sqnorm_finalize_kernel(CfSqnormArgs args)
 {
-    __shared__ double red[CF_FINALIZE_THREADS];
+    __shared__ double wave_sums[CF_FINALIZE_THREADS / 64];
     const uint32_t tid = threadIdx.x;
     const uint32_t k = blockIdx.x;
     const double *part = args.seg[k].partials;
     const uint64_t np = args.seg[k].n_chunks;
     double acc = 0.0;
     for (uint64_t i = tid; i < np; i += CF_FINALIZE_THREADS) acc += part[i];
-    red[tid] = acc;
-    __syncthreads();
-    for (uint32_t off = CF_FINALIZE_THREADS / 2; off > 0; off >>= 1) {
-        if (tid < off) red[tid] += red[tid + off];
-        __syncthreads();
-    }
+    const double omega = block_sum_fixed_order<CF_FINALIZE_THREADS>(acc, wave_sums);
     if (tid == 0) {
-        const double omega = red[0];
         args.omega_out[k] = omega;
         if (!(omega - omega == 0.0)) atomicOr(&args.words[CF_WORD_FLAGS], kFlagNonfiniteOmega);
     }
 }
 
 // Second pass, per tensor: workgroup t adds the partials of the chunks of tensor
-// t (chunks first[t] .. first[t+1]-1 of the stage) in binary64 in a fixed order.
+// t (chunks first[t] .. first[t+1]-1 of the stage) in a fixed order.
 __global__ __launch_bounds__(CF_THREADS) void cf_sqnorm_finalize_tensors_kernel(const double *partials,
                                                                                const uint32_t *first,
                                                                                double *tensor_out)
 {
-    __shared__ double red[CF_THREADS];
+    __shared__ double wave_sums[CF_WAVES];
     const uint32_t tid = threadIdx.x;
     const uint32_t lo = first[blockIdx.x];
     const uint32_t hi = first[blockIdx.x + 1];
     double acc = 0.0;
     for (uint32_t i = lo + tid; i < hi; i += CF_THREADS) acc += partials[i];
-    red[tid] = acc;
-    __syncthreads();
-    for (uint32_t off = CF_THREADS / 2; off > 0; off >>= 1) {
-        if (tid < off) red[tid] += red[tid + off];
-        __syncthreads();
-    }
-    if (tid == 0) tensor_out[blockIdx.x] = red[0];
+    const double total = block_sum_fixed_order<CF_THREADS>(acc, wave_sums);
+    if (tid == 0) tensor_out[blockIdx.x] = total;
 }
 
 // ---------------------------------------------------------------------------

@@ -154,7 +154,8 @@ def test_sqnorm_closed_forms(ctx, dev):
 def test_sqnorm_is_bitwise_reproducible_and_launch_shape_independent(dev):
     wl = workloads.make_workload(1, device=dev, shape=workloads.StageShape(192, 512, 2))
     results = []
-    for tuning in ({}, {"sqnorm_blocks_per_cu": 1}, {"sqnorm_blocks_per_cu": 3}, {"sqnorm_blocks_per_cu": 8}):
+    for tuning in ({}, {"sqnorm_blocks_per_cu": 1}, {"sqnorm_blocks_per_cu": 3}, {"sqnorm_blocks_per_cu": 8},
+                   {"sqnorm_blocks_per_cu": 65}):
         c = cf.Context(0, **tuning)
         handles = [cf.Stage(c, g) for g in wl.grads]
         for rep in range(3):
