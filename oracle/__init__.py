@@ -18,6 +18,8 @@ equation and Algorithm 1; section "CheckFree+: First and Last Stage Recovery"):
   blend_unrounded(prev, next, ..)             the same value in binary64, not narrowed
   copy_stage(src)                             bytewise copy (CheckFree+)
   copy_stage_ranges(src, dst, ranges)         slices of that copy (keeping a replica current piece by piece)
+  adam_step_with_sqnorm(w, m, v, g, ...)      one Adam step of a stage (the paper's optimizer) and omega of the
+                                              gradient it consumed, in the same pass
 """
 import ctypes
 import os
@@ -64,6 +66,10 @@ def _lib():
                                        ctypes.c_uint32]
         lib.cfo_common_scale.restype = None
         lib.cfo_common_scale.argtypes = [c_dp, c_dp]
+        lib.cfo_adam_step_f32.restype = ctypes.c_double
+        lib.cfo_adam_step_f32.argtypes = [ctypes.c_void_p, ctypes.c_void_p, ctypes.c_void_p, ctypes.c_void_p,
+                                          ctypes.c_uint64, ctypes.c_double, ctypes.c_double, ctypes.c_double,
+                                          ctypes.c_double, ctypes.c_uint64]
         lib.cfo_bf16_to_f64.restype = ctypes.c_double
         lib.cfo_bf16_to_f64.argtypes = [ctypes.c_uint16]
         lib.cfo_f64_to_bf16.restype = ctypes.c_uint16
@@ -191,6 +197,27 @@ def copy_stage_ranges(src, dst, ranges):
             raise ValueError("range outside the tensor")
         _lib().cfo_copy_range(d.ctypes.data, s.ctypes.data, int(first), int(count), s.itemsize)
     return dst
+
+
+def adam_step_with_sqnorm(weights, exp_avg, exp_avg_sq, grads, lr: float, beta1: float = 0.9,
+                          beta2: float = 0.999, eps: float = 1e-8, step: int = 1):
+    """One Adam step (no weight decay) over every tensor of a stage, IN PLACE on
+    the fp32 arrays of `weights`, `exp_avg` (m) and `exp_avg_sq` (v); `step` is t,
+    counted from 1.  Returns omega of the stage: the squared norm of `grads`,
+    tensors added in list order."""
+    if not (len(weights) == len(exp_avg) == len(exp_avg_sq) == len(grads)):
+        raise ValueError("the four tensor lists differ in length")
+    if step < 1:
+        raise ValueError("Adam counts its steps from 1")
+    omega = 0.0
+    for w, m, v, g in zip(weights, exp_avg, exp_avg_sq, grads):
+        for a in (w, m, v, g):
+            if a.dtype != np.float32 or not a.flags.c_contiguous or a.shape != w.shape:
+                raise ValueError("Adam step takes congruent contiguous float32 arrays")
+        omega += float(_lib().cfo_adam_step_f32(w.ctypes.data, m.ctypes.data, v.ctypes.data, g.ctypes.data,
+                                                w.size, float(lr), float(beta1), float(beta2), float(eps),
+                                                int(step)))
+    return omega
 
 
 def bf16_to_f64(bits: int) -> float:

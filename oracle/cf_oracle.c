@@ -284,6 +284,47 @@ void cfo_copy_range(void *dst, const void *src, uint64_t first, uint64_t count, 
     for (uint64_t k = 0; k < count * elem_bytes; ++k) d[k] = s[k];
 }
 
+/* ------------------------------------------------------------------ */
+/* omega as a by-product of the optimizer step                          */
+/* ------------------------------------------------------------------ */
+
+/* The paper trains with Adam, no weight decay, betas (0.9, 0.999) (appendix
+ * "Optimizers"), and every stage keeps omega = ||grad W^S||^2 of its last
+ * gradient (section "CheckFree: Memoryless Recovery").  The optimizer step is
+ * the one pass of an iteration that reads every gradient element anyway, so
+ * omega can leave it as a by-product.  This is that step for one fp32 tensor,
+ * written as Adam is defined (Kingma & Ba, "Adam: A Method for Stochastic
+ * Optimization", Algorithm 1), t counted from 1:
+ *
+ *     m_t = beta1 m_{t-1} + (1 - beta1) g
+ *     v_t = beta2 v_{t-1} + (1 - beta2) g^2
+ *     mhat = m_t / (1 - beta1^t),  vhat = v_t / (1 - beta2^t)
+ *     w_t = w_{t-1} - lr * mhat / (sqrt(vhat) + eps)
+ *
+ * Readings where paper and definition leave room: the moments and the weights
+ * are stored in binary32; all arithmetic is binary64; m_t and v_t are rounded
+ * once to binary32 when stored and the weight update uses those stored values
+ * (what a later step, or anyone else, would read back); w_t is rounded once.
+ * eps is added to the square root, outside it.  Returns this tensor's share
+ * of omega, the sum of g^2 in index order. */
+double cfo_adam_step_f32(float *w, float *m, float *v, const float *g, uint64_t n, double lr,
+                         double beta1, double beta2, double eps, uint64_t t)
+{
+    double correction1 = 1.0 - pow(beta1, (double)t);
+    double correction2 = 1.0 - pow(beta2, (double)t);
+    double omega = 0.0;
+    for (uint64_t k = 0; k < n; ++k) {
+        double grad = (double)g[k];
+        omega += grad * grad;
+        m[k] = (float)(beta1 * (double)m[k] + (1.0 - beta1) * grad);
+        v[k] = (float)(beta2 * (double)v[k] + (1.0 - beta2) * (grad * grad));
+        double mhat = (double)m[k] / correction1;
+        double vhat = (double)v[k] / correction2;
+        w[k] = (float)((double)w[k] - lr * mhat / (sqrt(vhat) + eps));
+    }
+    return omega;
+}
+
 int cfo_max_threads(void)
 {
 #ifdef _OPENMP

@@ -11,7 +11,8 @@ import pytest
 
 ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
 SRC = os.path.join(ROOT, "oracle", "cf_oracle.c")
-PIN_FILES = ["tests/test_oracle_sqnorm.py", "tests/test_oracle_blend.py", "tests/test_oracle_bf16_copy.py"]
+PIN_FILES = ["tests/test_oracle_sqnorm.py", "tests/test_oracle_blend.py", "tests/test_oracle_bf16_copy.py",
+             "tests/test_oracle_adam.py"]
 
 # (name, text in oracle/cf_oracle.c, replacement)
 MUTANTS = [
@@ -51,6 +52,22 @@ MUTANTS = [
      "if (threads < 1) threads = 1;\n#pragma omp parallel for num_threads(threads) schedule(static)\n    for (uint64_t k = 0; k < n; ++k)\n        out[k] = (float)"),
     ("range copy: source read from element 0", "const char *s = (const char *)src + first * elem_bytes;", "const char *s = (const char *)src;"),
     ("range copy: count taken as bytes", "for (uint64_t k = 0; k < count * elem_bytes; ++k) d[k] = s[k];", "for (uint64_t k = 0; k < count; ++k) d[k] = s[k];"),
+    ("adam: betas swapped in the moments", "m[k] = (float)(beta1 * (double)m[k] + (1.0 - beta1) * grad);",
+     "m[k] = (float)(beta2 * (double)m[k] + (1.0 - beta2) * grad);"),
+    ("adam: second moment of g instead of g^2", "(1.0 - beta2) * (grad * grad));", "(1.0 - beta2) * grad);"),
+    ("adam: first bias correction missing", "double mhat = (double)m[k] / correction1;", "double mhat = (double)m[k];"),
+    ("adam: second bias correction missing", "double vhat = (double)v[k] / correction2;", "double vhat = (double)v[k];"),
+    ("adam: step count off by one in the bias correction", "double correction1 = 1.0 - pow(beta1, (double)t);",
+     "double correction1 = 1.0 - pow(beta1, (double)t + 1.0);"),
+    ("adam: eps inside the square root", "(double)w[k] - lr * mhat / (sqrt(vhat) + eps)", "(double)w[k] - lr * mhat / sqrt(vhat + eps)"),
+    ("adam: ascent instead of descent", "(double)w[k] - lr * mhat", "(double)w[k] + lr * mhat"),
+    ("adam: no square root", "(double)w[k] - lr * mhat / (sqrt(vhat) + eps)", "(double)w[k] - lr * mhat / (vhat + eps)"),
+    ("adam: update from the old first moment",
+     "        m[k] = (float)(beta1 * (double)m[k] + (1.0 - beta1) * grad);\n        v[k] = (float)(beta2 * (double)v[k] + (1.0 - beta2) * (grad * grad));\n        double mhat = (double)m[k] / correction1;",
+     "        double mhat = (double)m[k] / correction1;\n        m[k] = (float)(beta1 * (double)m[k] + (1.0 - beta1) * grad);\n        v[k] = (float)(beta2 * (double)v[k] + (1.0 - beta2) * (grad * grad));"),
+    ("adam: omega of the first moment instead of the gradient", "omega += grad * grad;", "omega += (double)m[k] * (double)m[k];"),
+    ("adam: moments kept unrounded for the update", "double mhat = (double)m[k] / correction1;",
+     "double mhat = (beta1 * (double)m[k] + (1.0 - beta1) * grad) / correction1;"),
     ("copy: one byte short", "memcpy(dst, src, nbytes);\n        return;", "memcpy(dst, src, nbytes ? nbytes - 1 : 0);\n        return;"),
 ]
 
