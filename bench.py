@@ -14,6 +14,7 @@ metric is quoted on).  With the default configuration the same line also carries
     setup         cost of creating the five stage handles of a recovery, in
                   library-allocated and in caller-provided memory, and a recovery
                   timed from before the handles exist
+    optimizer_step  one stage's Adam step that also yields omega (no separate read of the gradients)
     replica_refresh (with --config 4) embedding + de-embedding refresh, whole and in slices
     ceilings      what two trivial kernels (flat buffer, no table) sustain on this GPU
     cpu_baseline  the CPU oracle on the host's cores
@@ -306,6 +307,8 @@ def main():
         result["setup"] = measure_setup(run, ctx, cf, torch)
     if args.config == 4 and not args.no_setup:
         result["replica_refresh"] = measure_replica_refresh(run, ctx, cf, torch)
+    if args.config != 4 and not args.no_setup:
+        result["optimizer_step"] = measure_optimizer_step(run, ctx, cf, torch)
     if not args.no_ceilings:
         result["ceilings"] = measure_ceilings(args, run, ctx, cf, torch)
     if not args.no_cpu_baseline:
@@ -427,6 +430,52 @@ def measure_setup(run, ctx, cf, torch, reps=15):
         "recovery_incl_setup_library_allocated_ms": med(r_owned),
         "recovery_incl_setup_caller_memory_ms": med(r_in),
     }
+
+
+def measure_optimizer_step(run, ctx, cf, torch, reps=20):
+    """Steady state: every stage keeps omega of its last gradient.  One stage's Adam step with omega as a
+    by-product (cf_adam_step_with_sqnorm: 4 reads + 3 writes of 4 bytes per element, nothing else), beside
+    the dedicated norm of the same gradients (what keeping omega current costs without the fused pass)."""
+    wl = run.wl
+    stream = torch.cuda.current_stream()
+    w = [t.clone() for t in wl.weights[wl.lost - 1]]
+    if w[0].dtype != torch.float32:
+        w = [t.float() for t in w]
+    g = wl.grads[wl.lost - 1]
+    m = [torch.zeros_like(t) for t in w]
+    v = [torch.zeros_like(t) for t in w]
+    sw, sm, sv, sg = (cf.Stage(ctx, x) for x in (w, m, v, g))
+    scratch = torch.empty(cf.adam_scratch_bytes(sg), dtype=torch.uint8, device=ctx.device)
+    omega = torch.zeros(1, dtype=torch.float64, device=ctx.device)
+    omega2 = torch.zeros(1, dtype=torch.float64, device=ctx.device)
+    step = [0]
+
+    def fused():
+        step[0] += 1
+        cf.cf_adam_step_with_sqnorm(ctx, sw, sm, sv, sg, 3e-4, 0.9, 0.999, 1e-8, step[0], scratch, omega, stream)
+
+    def timed(fn):
+        for _ in range(3):
+            fn()
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        e0.record(stream)
+        for _ in range(reps):
+            fn()
+        e1.record(stream)
+        e1.synchronize()
+        return e0.elapsed_time(e1) / reps
+
+    ms = timed(fused)
+    ms_norm = timed(lambda: cf.cf_stage_grad_sqnorm(ctx, [sg], omega2, stream))
+    nbytes = 28 * sg.numel
+    torch.cuda.synchronize()
+    rel = abs(omega.item() - omega2.item()) / max(omega2.item(), 1e-300)
+    return {"what": "Adam step of one stage with omega as a by-product (cf_adam_step_with_sqnorm); fp32 weights, "
+                    "moments and gradients",
+            "elements": sg.numel, "algorithmic_bytes": nbytes, "ms": round(ms, 5), "GBps": round(nbytes / ms / 1e6, 1),
+            "frac_of_hbm_peak": round(nbytes / ms / 1e6 / HBM_PEAK_GBPS, 4),
+            "dedicated_norm_of_the_same_gradients_ms": round(ms_norm, 5),
+            "omega_relative_difference_to_dedicated_norm": rel}
 
 
 def measure_replica_refresh(run, ctx, cf, torch, reps=20):

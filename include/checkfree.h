@@ -79,7 +79,8 @@ enum {
     CF_ERR_LIMIT = -5,           /* a size exceeds what the library supports */
     CF_ERR_HIP = -6,             /* a HIP runtime call failed (no device, bad stream, ...) */
     CF_ERR_ALIAS = -7,           /* output tensors overlap inputs other than element for element */
-    CF_ERR_CONTEXT = -8          /* handles belong to different contexts */
+    CF_ERR_CONTEXT = -8,         /* handles belong to different contexts */
+    CF_ERR_VALUE = -9            /* a scalar argument outside its domain */
 };
 
 /* Element types of stage tensors. */
@@ -253,6 +254,61 @@ CF_API cf_status cf_stage_grad_sqnorm_static(cf_ctx *ctx, const cf_tensor *grads
 
 /* Size in bytes of the per-GPU array cf_stage_grad_sqnorm_static works in. */
 CF_API uint64_t cf_static_scratch_bytes(void);
+
+/* ---- omega at no extra memory traffic: as a by-product of the optimizer step ---- */
+
+/* Scalars of one Adam step.  The paper trains with Adam, no weight decay, betas
+ * (0.9, 0.999) (appendix "Optimizers"); it names no epsilon (1e-8 is the value of
+ * the algorithm's authors). */
+typedef struct cf_adam_params {
+    double learning_rate;   /* finite */
+    double beta1, beta2;    /* in [0, 1) */
+    double epsilon;         /* >= 0, finite */
+    uint64_t step;          /* t of this step, counted from 1 */
+} cf_adam_params;
+
+/* Bytes of DEVICE scratch cf_adam_step_with_sqnorm needs for this gradient stage
+ * (8 bytes per KiB of gradients: one partial sum per tile).  0 for NULL. */
+CF_API uint64_t cf_adam_scratch_bytes(const cf_stage *grads);
+
+/* One Adam step over a whole stage AND omega of the gradient it consumed, in one
+ * pass over the gradients.  Paper: section "CheckFree: Memoryless Recovery" (every
+ * stage keeps omega = ||grad W^S||^2 of its last gradient, ready for a newcomer)
+ * and appendix "Optimizers" (Adam): the optimizer step reads every gradient
+ * element anyway, so omega leaves it as a by-product and keeping it current
+ * costs no memory traffic of its own.
+ *
+ * For every element (Kingma & Ba, Algorithm 1; t = params->step):
+ *   m <- beta1 m + (1 - beta1) g          v <- beta2 v + (1 - beta2) g^2
+ *   w <- w - lr (m / (1 - beta1^t)) / (sqrt(v / (1 - beta2^t)) + eps)
+ * in binary64; m and v are rounded once to binary32 when stored and the weight
+ * update uses the stored values; w is rounded once; eps is outside the root.
+ * The two bias corrections are applied as multiplications by their binary64
+ * reciprocals.
+ *
+ *   weights, exp_avg (m), exp_avg_sq (v)   updated in place; CF_F32 tensors only
+ *   grads                                   read only; CF_F32; its handle's scratch
+ *                                           is used as by cf_stage_grad_sqnorm
+ *   d_scratch                               DEVICE, cf_adam_scratch_bytes(grads)
+ *                                           bytes, 8-byte aligned, caller's
+ *   d_omega_out                             DEVICE, one double: the sum of g^2 over
+ *                                           the stage, bit-reproducible; the same
+ *                                           terms as cf_stage_grad_sqnorm adds, in
+ *                                           another fixed order, so equal to it to
+ *                                           within rounding (relative 1e-14), not
+ *                                           bit for bit
+ *
+ * The four stages must agree tensor by tensor in numel (CF_ERR_SHAPE_MISMATCH);
+ * none of weights, exp_avg, exp_avg_sq may overlap another of the four other
+ * than element for element (CF_ERR_ALIAS).  Enqueues three kernels on `stream`;
+ * allocates nothing, copies nothing, does not wait.  A non-finite omega raises
+ * CF_FLAG_NONFINITE_OMEGA.
+ * Errors: CF_ERR_NULL, CF_ERR_CONTEXT, CF_ERR_SHAPE_MISMATCH, CF_ERR_DTYPE,
+ * CF_ERR_ALIAS, CF_ERR_VALUE (a parameter outside its domain), CF_ERR_LIMIT
+ * (scratch too small), CF_ERR_ALIGN, CF_ERR_HIP. */
+CF_API cf_status cf_adam_step_with_sqnorm(cf_ctx *ctx, cf_stage *weights, cf_stage *exp_avg, cf_stage *exp_avg_sq,
+                                          const cf_stage *grads, const cf_adam_params *params, void *d_scratch,
+                                          uint64_t scratch_bytes, double *d_omega_out, void *stream);
 
 /* Rebuilds a lost intermediate stage from its two neighbours:
  *   lost[t][k] = (w_p * prev[t][k] + w_n * next[t][k]) / (w_p + w_n)

@@ -26,7 +26,7 @@ LIB_PATH = os.path.join(_PKG, "libcheckfree.so")
 
 CF_OK = 0
 CF_ERR_NULL, CF_ERR_SHAPE_MISMATCH, CF_ERR_DTYPE, CF_ERR_ALIGN = -1, -2, -3, -4
-CF_ERR_LIMIT, CF_ERR_HIP, CF_ERR_ALIAS, CF_ERR_CONTEXT = -5, -6, -7, -8
+CF_ERR_LIMIT, CF_ERR_HIP, CF_ERR_ALIAS, CF_ERR_CONTEXT, CF_ERR_VALUE = -5, -6, -7, -8, -9
 CF_F32, CF_BF16 = 0, 1
 CF_FLAG_DEGENERATE_OMEGA, CF_FLAG_NONFINITE_OMEGA = 1, 2
 
@@ -40,12 +40,18 @@ EXPORTS = (
     "cf_stage_grad_sqnorm_per_tensor",
     "cf_workspace_bytes", "cf_ctx_create_in", "cf_stage_table_bytes", "cf_stage_create_in",
     "cf_copy_stage_range", "cf_stage_grad_sqnorm_static", "cf_static_scratch_bytes",
+    "cf_adam_scratch_bytes", "cf_adam_step_with_sqnorm",
 )
 
 
 class CfTensor(ctypes.Structure):
     _fields_ = [("data", ctypes.c_void_p), ("numel", ctypes.c_uint64),
                 ("dtype", ctypes.c_int32), ("reserved", ctypes.c_int32)]
+
+
+class CfAdamParams(ctypes.Structure):
+    _fields_ = [("learning_rate", ctypes.c_double), ("beta1", ctypes.c_double), ("beta2", ctypes.c_double),
+                ("epsilon", ctypes.c_double), ("step", ctypes.c_uint64)]
 
 
 class CfTuning(ctypes.Structure):
@@ -94,6 +100,10 @@ def load_library():
     lib.cf_stage_grad_sqnorm_static.argtypes = [vp, ctypes.POINTER(CfTensor), u32, vp, vp]
     lib.cf_static_scratch_bytes.restype = u64
     lib.cf_static_scratch_bytes.argtypes = []
+    lib.cf_adam_scratch_bytes.restype = u64
+    lib.cf_adam_scratch_bytes.argtypes = [vp]
+    lib.cf_adam_step_with_sqnorm.restype = i32
+    lib.cf_adam_step_with_sqnorm.argtypes = [vp, vp, vp, vp, vp, ctypes.POINTER(CfAdamParams), vp, u64, vp, vp]
     lib.cf_ctx_destroy.restype = i32
     lib.cf_ctx_destroy.argtypes = [vp]
     lib.cf_stage_create.restype = i32
@@ -336,6 +346,31 @@ def cf_stage_grad_sqnorm_static(ctx: Context, grads, out, stream=None):
     desc = tensor_descriptors(list(grads))
     _check(load_library().cf_stage_grad_sqnorm_static(ctx._h, desc, len(grads), _omega_ptr(ctx, out),
                                                       _stream_ptr(stream)), "cf_stage_grad_sqnorm_static")
+    return out
+
+
+def adam_scratch_bytes(grads: Stage) -> int:
+    return int(load_library().cf_adam_scratch_bytes(grads._h))
+
+
+def cf_adam_step_with_sqnorm(ctx: Context, weights: Stage, exp_avg: Stage, exp_avg_sq: Stage, grads: Stage,
+                             lr: float, beta1: float = 0.9, beta2: float = 0.999, eps: float = 1e-8, step: int = 1,
+                             scratch=None, out=None, stream=None):
+    """One Adam step of a stage (weights, exp_avg, exp_avg_sq updated in place) and,
+    from the same pass over `grads`, omega of the stage as a one-element float64
+    device tensor.  `scratch` is a uint8 device tensor of adam_scratch_bytes(grads)
+    bytes (allocated here if not given).  Asynchronous on the stream."""
+    import torch
+    need = adam_scratch_bytes(grads)
+    if scratch is None:
+        scratch = torch.empty(need, dtype=torch.uint8, device=ctx.device)
+    if out is None:
+        out = torch.empty(1, dtype=torch.float64, device=ctx.device)
+    params = CfAdamParams(float(lr), float(beta1), float(beta2), float(eps), int(step))
+    _check(load_library().cf_adam_step_with_sqnorm(
+        ctx._h, weights._h, exp_avg._h, exp_avg_sq._h, grads._h, ctypes.byref(params),
+        ctypes.c_void_p(scratch.data_ptr() if scratch.numel() else None), scratch.numel(), _omega_ptr(ctx, out),
+        _stream_ptr(stream)), "cf_adam_step_with_sqnorm")
     return out
 
 

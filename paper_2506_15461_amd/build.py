@@ -12,7 +12,7 @@ PKG = os.path.dirname(os.path.abspath(__file__))
 ROOT = os.path.dirname(PKG)
 CSRC = os.path.join(PKG, "csrc")
 LIB = os.path.join(PKG, "libcheckfree.so")
-HIP_SOURCES = ["cf_kernels.hip"]
+HIP_SOURCES = ["cf_kernels.hip", "cf_adam_kernels.hip"]
 HOST_SOURCES = ["cf_api.cpp"]
 
 

@@ -5,6 +5,7 @@
 
 #include <algorithm>
 #include <atomic>
+#include <cmath>
 #include <cstring>
 #include <mutex>
 #include <new>
@@ -297,6 +298,7 @@ const char *cf_status_string(cf_status status)
     case CF_ERR_HIP: return "CF_ERR_HIP: HIP runtime call failed";
     case CF_ERR_ALIAS: return "CF_ERR_ALIAS: output overlaps an input other than element for element";
     case CF_ERR_CONTEXT: return "CF_ERR_CONTEXT: handles belong to different contexts";
+    case CF_ERR_VALUE: return "CF_ERR_VALUE: scalar argument outside its domain";
     default: return "unknown cf_status";
     }
 }
@@ -671,6 +673,72 @@ cf_status cf_recover_stage_with_weights(cf_ctx *ctx, const cf_stage *prev, const
                                         double omega_prev, double omega_next, cf_stage *lost, void *stream)
 {
     return recover_impl(ctx, prev, next, nullptr, nullptr, omega_prev, omega_next, lost, stream);
+}
+
+uint64_t cf_adam_scratch_bytes(const cf_stage *grads)
+{
+    if (!grads) return 0;
+    return align_up(((uint64_t)grads->n_chunks << grads->ctx->tile_shift) * sizeof(double));
+}
+
+cf_status cf_adam_step_with_sqnorm(cf_ctx *ctx, cf_stage *weights, cf_stage *exp_avg, cf_stage *exp_avg_sq,
+                                   const cf_stage *grads, const cf_adam_params *params, void *d_scratch,
+                                   uint64_t scratch_bytes, double *d_omega_out, void *stream)
+{
+    if (!ctx || !weights || !exp_avg || !exp_avg_sq || !grads || !params || !d_omega_out) return CF_ERR_NULL;
+    const cf_stage *all[4] = {weights, exp_avg, exp_avg_sq, grads};
+    for (const cf_stage *s : all)
+        if (s->ctx != ctx) return CF_ERR_CONTEXT;
+    const cf_adam_params &a = *params;
+    const bool ok = std::isfinite(a.learning_rate) && a.beta1 >= 0.0 && a.beta1 < 1.0 && a.beta2 >= 0.0 &&
+                    a.beta2 < 1.0 && std::isfinite(a.epsilon) && a.epsilon >= 0.0 && a.step >= 1;
+    if (!ok) return CF_ERR_VALUE;
+    for (const cf_stage *s : all)
+        for (const HostTensor &t : s->tensors)
+            if (t.dtype != CF_F32) return CF_ERR_DTYPE;
+    // Every stage written to against every other of the four: congruent, and no byte shared except
+    // element for element.
+    cf_stage *outs[3] = {weights, exp_avg, exp_avg_sq};
+    for (cf_stage *o : outs)
+        for (const cf_stage *i : all) {
+            if (i == o) continue;
+            cf_status st = checked_pair(ctx, i, o);
+            if (st != CF_OK) return st;
+        }
+    const uint64_t need = cf_adam_scratch_bytes(grads);
+    if (grads->n_chunks) {
+        if (!d_scratch) return CF_ERR_NULL;
+        if (scratch_bytes < need) return CF_ERR_LIMIT;
+        if (reinterpret_cast<uint64_t>(d_scratch) % 8 != 0) return CF_ERR_ALIGN;
+    }
+    CfAdamArgs p;
+    p.beta1 = a.beta1;
+    p.one_minus_beta1 = 1.0 - a.beta1;
+    p.beta2 = a.beta2;
+    p.one_minus_beta2 = 1.0 - a.beta2;
+    p.rcp_correction1 = 1.0 / (1.0 - std::pow(a.beta1, (double)a.step));
+    p.rcp_correction2 = 1.0 / (1.0 - std::pow(a.beta2, (double)a.step));
+    p.lr = a.learning_rate;
+    p.eps = a.epsilon;
+    DeviceGuard guard(ctx->device);
+    if (!guard.ok()) return CF_ERR_HIP;
+    hipStream_t s = static_cast<hipStream_t>(stream);
+    if (grads->n_chunks &&
+        cf_launch_adam_sqnorm(weights->d_chunks, exp_avg->d_chunks, exp_avg_sq->d_chunks, grads->d_chunks,
+                              grads->n_chunks, ctx->tile_shift, p, static_cast<double *>(d_scratch), grads->d_partials,
+                              s) != hipSuccess)
+        return CF_ERR_HIP;
+    CfSqnormArgs args;
+    std::memset(&args, 0, sizeof args);
+    args.seg[0].chunks = grads->d_chunks;
+    args.seg[0].partials = grads->d_partials;
+    args.seg[0].n_chunks = grads->n_chunks;
+    args.n_seg = 1;
+    args.total_chunks = grads->n_chunks;
+    args.omega_out = d_omega_out;
+    args.words = ctx->d_words;
+    if (cf_launch_sqnorm_finalize(args, s) != hipSuccess) return CF_ERR_HIP;
+    return CF_OK;
 }
 
 double cf_recovered_learning_rate(double learning_rate) { return CF_RECOVERY_LR_FACTOR * learning_rate; }

@@ -96,6 +96,24 @@ hipError_t cf_launch_blend(const CfChunk *prev, const CfChunk *next, const CfChu
                            uint32_t tile_shift, const double *d_omega_prev, const double *d_omega_next,
                            double h_omega_prev, double h_omega_next, uint32_t *words, hipStream_t stream);
 
+// Scalars of one Adam step, prepared by the host: the bias corrections enter as reciprocals.
+struct CfAdamArgs {
+    double beta1, one_minus_beta1;
+    double beta2, one_minus_beta2;
+    double rcp_correction1, rcp_correction2;   // 1 / (1 - beta^t)
+    double lr, eps;
+};
+
+// One Adam step over four congruent fp32 stages, one workgroup per tile; every tile's sum of
+// squared gradients goes to tile_partials[(chunk << tile_shift) + tile], and a second kernel adds a
+// chunk's tiles into partials[chunk] (the slots the norm's second pass reads).
+hipError_t cf_launch_adam_sqnorm(const CfChunk *weights, const CfChunk *exp_avg, const CfChunk *exp_avg_sq,
+                                 const CfChunk *grads, uint32_t n_chunks, uint32_t tile_shift, const CfAdamArgs &p,
+                                 double *tile_partials, double *partials, hipStream_t stream);
+
+// The norm's second pass alone (one workgroup per stage of `args`), for partials that are already there.
+hipError_t cf_launch_sqnorm_finalize(const CfSqnormArgs &args, hipStream_t stream);
+
 // Chunks first_chunk .. first_chunk + n_chunks - 1 of the two tables.
 hipError_t cf_launch_copy(const CfChunk *src, const CfChunk *dst, uint32_t first_chunk, uint32_t n_chunks,
                           uint32_t tile_shift, hipStream_t stream);

@@ -15,6 +15,7 @@
 
 #include <mutex>
 
+#include "cf_device.h"
 #include "cf_kernels.h"
 
 // Device memory for callers that cannot allocate (code under graph capture, tight serving loops):
@@ -30,67 +31,6 @@ static __device__ __align__(256) unsigned char scratch[CF_STATIC_SCRATCH_BYTES];
 
 namespace {
 
-typedef float f32x4 __attribute__((ext_vector_type(4)));
-typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
-
-// Tensor data is always device (global) memory; saying so keeps the compiler
-// from emitting generic-address (flat) memory instructions.
-#define CF_GLOBAL __attribute__((address_space(1)))
-typedef CF_GLOBAL const float *gcf32;
-typedef CF_GLOBAL float *gf32;
-typedef CF_GLOBAL const f32x4 *gcf32x4;
-typedef CF_GLOBAL f32x4 *gf32x4;
-typedef CF_GLOBAL const u32x4 *gcu32x4;
-typedef CF_GLOBAL u32x4 *gu32x4;
-typedef CF_GLOBAL const uint16_t *gcu16;
-typedef CF_GLOBAL uint16_t *gu16;
-typedef CF_GLOBAL const uint32_t *gcu32;
-typedef CF_GLOBAL uint32_t *gu32;
-typedef CF_GLOBAL const unsigned char *gcu8;
-typedef CF_GLOBAL unsigned char *gu8;
-
-constexpr uint32_t kFlagDegenerateOmega = 1u;
-constexpr uint32_t kFlagNonfiniteOmega = 2u;
-constexpr uint32_t kDtypeF32 = 0u;
-
-// ---------------------------------------------------------------------------
-// Wavefront reduction on the DPP cross-lane path (no LDS traffic).
-// ---------------------------------------------------------------------------
-
-template <int kCtrl>
-__device__ __forceinline__ double dpp_permute(double v)
-{
-    const int lo = __builtin_amdgcn_update_dpp(0, __double2loint(v), kCtrl, 0xF, 0xF, true);
-    const int hi = __builtin_amdgcn_update_dpp(0, __double2hiint(v), kCtrl, 0xF, 0xF, true);
-    return __hiloint2double(hi, lo);
-}
-
-__device__ __forceinline__ double read_lane(double v, int lane)
-{
-    return __hiloint2double(__builtin_amdgcn_readlane(__double2hiint(v), lane),
-                            __builtin_amdgcn_readlane(__double2loint(v), lane));
-}
-
-// Sum of v over the 64 lanes, same value in a fixed association on every run:
-// butterfly inside each row of 16 lanes (quad_perm [1,0,3,2], quad_perm
-// [2,3,0,1], row_half_mirror, row_mirror; a binary64 value moves as its two
-// halves), then the four row sums as (r0 + r1) + (r2 + r3).
-__device__ __forceinline__ double wave_sum(double v)
-{
-    v += dpp_permute<0xB1>(v);
-    v += dpp_permute<0x4E>(v);
-    v += dpp_permute<0x141>(v);
-    v += dpp_permute<0x140>(v);
-    return (read_lane(v, 0) + read_lane(v, 16)) + (read_lane(v, 32) + read_lane(v, 48));
-}
-
-// Elements before the first 16-byte boundary at or after `addr`.
-__device__ __forceinline__ uint32_t head_elems(uint64_t addr, uint32_t elem_bytes, uint32_t len)
-{
-    uint32_t h = (uint32_t)((16u - (uint32_t)(addr & 15u)) & 15u) / elem_bytes;
-    return h < len ? h : len;
-}
-
 // ---------------------------------------------------------------------------
 // omega = ||grad W^S||^2, all stages of a launch in one grid.
 // ---------------------------------------------------------------------------
@@ -103,12 +43,6 @@ __device__ __forceinline__ uint32_t head_elems(uint64_t addr, uint32_t elem_byte
 // memory stream leaves room for, so the squares of binary32 values can neither
 // underflow nor overflow and the rounding error of omega does not depend on how
 // long a lane's chain is.
-__device__ __forceinline__ void sq_acc(double &acc, float v)
-{
-    const double x = (double)v;
-    acc = __builtin_fma(x, x, acc);
-}
-
 template <int kUnroll>
 __device__ __forceinline__ double chunk_sqsum_f32(gcf32 p, uint32_t len, uint32_t tid)
 {
@@ -218,24 +152,6 @@ __global__ __launch_bounds__(CF_THREADS) void cf_sqnorm_partials_kernel(CfSqnorm
                 (wave_part[parity][0] + wave_part[parity][1]) + (wave_part[parity][2] + wave_part[parity][3]);
         parity ^= 1u;
     }
-}
-
-// Sum over a workgroup of kThreads threads in a fixed order: the wavefront
-// butterfly, then the wavefront sums added one after the other by thread 0 (one
-// barrier).  The result is valid in thread 0 only.
-template <int kThreads>
-__device__ __forceinline__ double block_sum_fixed_order(double v, double *wave_sums)
-{
-    const uint32_t tid = threadIdx.x;
-    const double w = wave_sum(v);
-    if ((tid & 63u) == 0) wave_sums[tid >> 6] = w;
-    __syncthreads();
-    double total = 0.0;
-    if (tid == 0) {
-#pragma unroll
-        for (int k = 0; k < kThreads / 64; ++k) total += wave_sums[k];
-    }
-    return total;
 }
 
 // Second pass, stream-ordered after the first: workgroup k adds the partials of
@@ -572,6 +488,12 @@ hipError_t cf_static_scratch_address(int device, void **ptr)
     return hipSuccess;
 }
 
+hipError_t cf_launch_sqnorm_finalize(const CfSqnormArgs &args, hipStream_t stream)
+{
+    hipLaunchKernelGGL(cf_sqnorm_finalize_kernel, dim3(args.n_seg), dim3(CF_FINALIZE_THREADS), 0, stream, args);
+    return hipGetLastError();
+}
+
 hipError_t cf_launch_sqnorm(const CfSqnormArgs &args, uint32_t grid, hipStream_t stream)
 {
     if (args.total_chunks != 0) {
@@ -579,8 +501,7 @@ hipError_t cf_launch_sqnorm(const CfSqnormArgs &args, uint32_t grid, hipStream_t
         hipError_t e = hipGetLastError();
         if (e != hipSuccess) return e;
     }
-    hipLaunchKernelGGL(cf_sqnorm_finalize_kernel, dim3(args.n_seg), dim3(CF_FINALIZE_THREADS), 0, stream, args);
-    return hipGetLastError();
+    return cf_launch_sqnorm_finalize(args, stream);
 }
 
 hipError_t cf_launch_sqnorm_tensors(const double *partials, const uint32_t *tensor_first_chunk, uint32_t num_tensors,
