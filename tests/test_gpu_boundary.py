@@ -290,3 +290,71 @@ def test_blend_with_omegas_at_the_ends_of_the_binary64_range(dev, dtype):
         torch.cuda.synchronize()
         assert all(np.array_equal(x, y) for x, y in zip(np_stage(out), got))
     assert c.read_flags() == 0
+
+
+def test_the_same_gradients_through_two_handles_on_two_streams_at_once(dev):
+    """A handle's block holds the norm's scratch, so ONE handle must not be in two norm calls that may overlap;
+    the supported way to take the norm of the same tensors concurrently is one handle per stream."""
+    c = cf.Context(0)
+    wl = workloads.make_workload(1, device=dev, shape=workloads.StageShape(256, 704, 2), seed=616)
+    grads = wl.grads[0]
+    ref = oracle.stage_grad_sqnorm(np_stage(grads))
+    handles = [cf.Stage(c, grads), cf.Stage(c, grads)]
+    streams = [torch.cuda.Stream(), torch.cuda.Stream()]
+    outs = [torch.zeros(1, dtype=torch.float64, device=dev) for _ in range(2)]
+    torch.cuda.synchronize()
+    for rep in range(20):
+        for h, s, o in zip(handles, streams, outs):
+            cf.cf_stage_grad_sqnorm(c, [h], o, s)
+    torch.cuda.synchronize()
+    assert outs[0].item() == outs[1].item()
+    assert abs(outs[0].item() - ref) <= 1e-12 * ref
+    assert c.read_flags() == 0
+
+
+def test_hot_calls_from_several_host_threads(dev):
+    """Four host threads, each with its own stream, context and handles, run whole recoveries at the same
+    time; every result must be the one a single thread gets."""
+    import threading
+    n_threads = 4
+    wls = [workloads.make_workload(1, device=dev, shape=workloads.StageShape(128, 352, 2), seed=700 + i)
+           for i in range(n_threads)]
+    wants = []
+    for wl in wls:
+        refs = [oracle.stage_grad_sqnorm(np_stage(wl.grads[s])) for s in (0, 2)]
+        wants.append((refs, oracle.recover_stage_weighted_avg(np_stage(wl.weights[0]), np_stage(wl.weights[2]), *refs)))
+    torch.cuda.synchronize()
+    errors, omegas = [], [None] * n_threads
+
+    def work(i):
+        try:
+            torch.cuda.set_device(dev)
+            wl = wls[i]
+            s = torch.cuda.Stream()
+            with torch.cuda.stream(s):
+                c = cf.Context(0, stream=s)
+                for rep in range(10):
+                    prev, nxt, lost = (cf.Stage(c, wl.weights[k], stream=s) for k in (0, 2, 1))
+                    gp, gn = cf.Stage(c, wl.grads[0], stream=s), cf.Stage(c, wl.grads[2], stream=s)
+                    om = cf.cf_stage_grad_sqnorm(c, [gp, gn], stream=s)
+                    cf.cf_recover_stage_weighted_avg(c, prev, nxt, om[0:1], om[1:2], lost, stream=s)
+                    s.synchronize()
+                    for h in (prev, nxt, lost, gp, gn):
+                        h.close()
+                omegas[i] = om.cpu().numpy()
+                assert c.read_flags(stream=s) == 0
+        except Exception as e:                       # reported by the main thread
+            errors.append((i, repr(e)))
+
+    threads = [threading.Thread(target=work, args=(i,)) for i in range(n_threads)]
+    for t in threads:
+        t.start()
+    for t in threads:
+        t.join()
+    assert not errors, errors
+    torch.cuda.synchronize()
+    for i, (wl, (refs, want)) in enumerate(zip(wls, wants)):
+        for k in range(2):
+            assert abs(omegas[i][k] - refs[k]) <= 1e-12 * refs[k]
+        for g, x in zip(np_stage(wl.weights[1]), want):
+            assert int(em.ulp_distance(g.reshape(-1), x.reshape(-1)).max()) <= 2
