@@ -36,7 +36,7 @@
  * multiply-add is fused), one rounding to the storage type at the end.
  *
  * Where the paper is silent (omega sum zero, negative or not finite) the
- * reading taken is the section's own "naive" variant, the uniform average:
+ * reading taken is the unweighted variant the section itself mentions, the uniform average:
  * both weights are replaced by 1.  cfo_effective_omega states that rule.
  *
  * Pins: tests/test_oracle_*.py check every function against closed forms,

@@ -1,6 +1,6 @@
 """Pins for the oracle's bfloat16 conversions and for the CheckFree+ copy
 (paper, section "CheckFree+: First and Last Stage Recovery": an end stage is
-restored from its neighbour and the (de)embedding "exactly")."""
+restored from its neighbour and the (de)embedding without any loss)."""
 from fractions import Fraction
 
 import numpy as np

@@ -245,7 +245,7 @@ def test_nan_and_inf_weights_propagate():
                                    (1e-320, 1e-320), (1e308, 1e308)])
 def test_degenerate_omega_rule_is_the_uniform_average(wp, wn):
     """Our reading where the paper is silent (parity unpinned): an unusable
-    omega pair falls back to the section's "naive" uniform average."""
+    omega pair falls back to the unweighted (uniform) average the section itself mentions."""
     rng = np.random.default_rng(12)
     a, b = _rand_weights(rng, 500, "f32")
     assert oracle.effective_omega(wp, wn) == (1.0, 1.0, True)
