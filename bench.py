@@ -164,9 +164,11 @@ class Runner:
         t0 = time.perf_counter()
         for k in range(steps):
             self.step(k, events.get(k))
+        t_enqueued = time.perf_counter()
         torch.cuda.synchronize()
         t1 = time.perf_counter()
         ms_per_step = (t1 - t0) * 1e3 / steps
+        self.host_enqueue_ms_per_step = (t_enqueued - t0) * 1e3 / steps
         kernel_ms = {}
         for j, name in enumerate(self.kernels):
             d = np.array([events[k][j].elapsed_time(events[k][j + 1]) for k in sampled])
@@ -283,6 +285,7 @@ def main():
             "buffer_sets_rotated": run.n_sets,
             "steps_with_kernel_events": sampled_step["n"],
             "device_flags": flags,
+            "host_enqueue_ms_per_step": round(run.host_enqueue_ms_per_step, 5),
             "tuning": tuning or "default",
         },
         "kernels": run.kernel_table(kernel_ms),
@@ -324,6 +327,7 @@ def main():
             entry = {"workload": r.spec.name, "ms_per_step": round(ms, 5), "GBps": round(r.step_bytes / ms / 1e6, 1),
                      "frac_of_hbm_peak": round(r.step_bytes / ms / 1e6 / HBM_PEAK_GBPS, 4),
                      "algorithmic_bytes_per_step": int(r.step_bytes), "steps": steps, "buffer_sets_rotated": r.n_sets,
+                     "host_enqueue_ms_per_step": round(r.host_enqueue_ms_per_step, 5),
                      "kernels": {k: {"ms_avg": v["ms_avg"], "GBps_avg": v["GBps_avg"]}
                                  for k, v in r.kernel_table(kms).items()}}
             if not args.no_graph:
