@@ -52,11 +52,15 @@ __device__ __forceinline__ double chunk_sqsum_f32(gcf32 p, uint32_t len, uint32_
     gcf32x4 q = (gcf32x4)(p + head);
     const uint32_t rem = len - head;
     const uint32_t n4 = rem >> 2;
-    uint32_t i = tid;
-    for (; i + (kUnroll - 1) * CF_THREADS < n4; i += kUnroll * CF_THREADS) {
+    // kUnroll loads in flight in every round, the last round included: a lane whose vector lies past the
+    // chunk's end takes zeros instead, and adding the square of zero changes no accumulator.
+    for (uint32_t base = tid; base < n4 + tid; base += kUnroll * CF_THREADS) {
         f32x4 v[kUnroll];
 #pragma unroll
-        for (int u = 0; u < kUnroll; ++u) v[u] = __builtin_nontemporal_load(q + i + u * CF_THREADS);
+        for (int u = 0; u < kUnroll; ++u) {
+            const uint32_t i = base + u * CF_THREADS;
+            v[u] = (i < n4) ? __builtin_nontemporal_load(q + i) : (f32x4)(0.f);
+        }
 #pragma unroll
         for (int u = 0; u < kUnroll; ++u) {
             sq_acc(a0, v[u].x);
@@ -64,13 +68,6 @@ __device__ __forceinline__ double chunk_sqsum_f32(gcf32 p, uint32_t len, uint32_
             sq_acc(a2, v[u].z);
             sq_acc(a3, v[u].w);
         }
-    }
-    for (; i < n4; i += CF_THREADS) {
-        const f32x4 v = __builtin_nontemporal_load(q + i);
-        sq_acc(a0, v.x);
-        sq_acc(a1, v.y);
-        sq_acc(a2, v.z);
-        sq_acc(a3, v.w);
     }
     const uint32_t tail = rem & 3u;
     if (tid < tail) sq_acc(a0, p[head + (n4 << 2) + tid]);
@@ -94,11 +91,13 @@ __device__ __forceinline__ double chunk_sqsum_bf16(gcu16 p, uint32_t len, uint32
     gcu32x4 q = (gcu32x4)(p + head);
     const uint32_t rem = len - head;
     const uint32_t n8 = rem >> 3;
-    uint32_t i = tid;
-    for (; i + (kUnroll - 1) * CF_THREADS < n8; i += kUnroll * CF_THREADS) {
+    for (uint32_t base = tid; base < n8 + tid; base += kUnroll * CF_THREADS) {
         u32x4 v[kUnroll];
 #pragma unroll
-        for (int u = 0; u < kUnroll; ++u) v[u] = __builtin_nontemporal_load(q + i + u * CF_THREADS);
+        for (int u = 0; u < kUnroll; ++u) {
+            const uint32_t i = base + u * CF_THREADS;
+            v[u] = (i < n8) ? __builtin_nontemporal_load(q + i) : (u32x4)(0u);
+        }
 #pragma unroll
         for (int u = 0; u < kUnroll; ++u) {
             sq_acc_bf16_word(a0, a1, v[u].x);
@@ -106,13 +105,6 @@ __device__ __forceinline__ double chunk_sqsum_bf16(gcu16 p, uint32_t len, uint32
             sq_acc_bf16_word(a0, a1, v[u].z);
             sq_acc_bf16_word(a2, a3, v[u].w);
         }
-    }
-    for (; i < n8; i += CF_THREADS) {
-        const u32x4 v = __builtin_nontemporal_load(q + i);
-        sq_acc_bf16_word(a0, a1, v.x);
-        sq_acc_bf16_word(a2, a3, v.y);
-        sq_acc_bf16_word(a0, a1, v.z);
-        sq_acc_bf16_word(a2, a3, v.w);
     }
     const uint32_t tail = rem & 7u;
     if (tid < tail) sq_acc(a0, __uint_as_float((uint32_t)p[head + (n8 << 3) + tid] << 16));
