@@ -111,7 +111,7 @@ typedef struct cf_tuning {
                                       results of the norm differ between chunk sizes only in the last bits */
     uint32_t sqnorm_blocks_per_cu; /* grid of the norm's first pass: 1..64 = at most that many workgroups per
                                       compute unit; 65 = one workgroup per chunk; default 0 = chosen by the
-                                      size of the launch (one per chunk below 1 GiB of gradients, two per
+                                      size of the launch (one per chunk below 512 MiB of gradients, two per
                                       compute unit from there on).  Never changes a result bit. */
     uint32_t reserved0;
     uint32_t reserved1;

@@ -22,7 +22,7 @@ constexpr uint32_t kMaxChunkBytes = 4u << 20;
 constexpr uint32_t kDefaultSqnormBlocksPerCu = 0;     // 0: chosen by the size of the launch
 constexpr uint32_t kOnePerChunk = 65;                 // tuning value that forces one workgroup per chunk
 constexpr uint32_t kCappedGridPerCu = 2;
-constexpr uint64_t kCappedGridFromBytes = 1ull << 30;
+constexpr uint64_t kCappedGridFromBytes = 512ull << 20;
 constexpr uint64_t kMaxChunksPerStage = 1ull << 31;
 constexpr uint64_t kMaxGrid = (1ull << 31) - 1;
 constexpr size_t kCtxWordBytes = CF_CTX_WORDS * sizeof(uint32_t);
@@ -261,9 +261,9 @@ hipError_t enqueue_table(const cf_ctx *ctx, const cf_tensor *tensors, uint32_t n
 
 // Grid of the norm's first pass.  The partials are per chunk, so the result does not depend on this
 // choice; only the speed does.  Measured on this chip: up to a few thousand chunks one workgroup per
-// chunk is fastest (the launch is over before a capped grid has paid for itself); from about 1 GiB of
-// gradients on, 512 resident workgroups walking the chunk list are 1-3 % faster than 12 000 and more
-// short-lived ones.
+// chunk is as fast or faster (the launch is over before a capped grid has paid for itself); from about
+// half a GiB of gradients on, 512 resident workgroups walking the chunk list are 1-3 % faster than
+// thousands of short-lived ones.
 uint32_t sqnorm_grid(const cf_ctx *ctx, uint32_t n_chunks)
 {
     uint64_t g = n_chunks;
