@@ -96,8 +96,12 @@ enum {
 };
 
 /* One contiguous tensor in device memory.  `data` must be aligned to the element
- * size (16-byte alignment is not required; 16-byte aligned tensors take the fast
- * path).  numel may be 0 (then data may be NULL). */
+ * size; nothing more is required.  Corresponding tensors of the stages of one
+ * call whose addresses agree modulo 16 (tensors from an allocator always do;
+ * views into flat buffers at the same offset do) are moved 16 bytes per lane,
+ * with the vector body placed on 128-byte boundaries of the written tensor, at
+ * the same speed whatever the offset; others are moved element by element.
+ * numel may be 0 (then data may be NULL). */
 typedef struct cf_tensor {
     void *data;      /* device pointer */
     uint64_t numel;  /* number of elements */

@@ -82,7 +82,7 @@ __global__ __launch_bounds__(CF_TILE_THREADS) void cf_adam_sqnorm_kernel(const C
             }
         }
     } else {
-        const uint32_t head = head_elems(cg.addr, 4u, len);
+        const uint32_t head = head_elems(cw.addr, 4u, len);   // whole lines for the streams that are written
         const uint32_t rem = len - head;
         const uint32_t n4 = rem >> 2;
         const uint32_t vi = tile * CF_TILE_THREADS + tid;
@@ -108,7 +108,7 @@ __global__ __launch_bounds__(CF_TILE_THREADS) void cf_adam_sqnorm_kernel(const C
             __builtin_nontemporal_store(w, (gf32x4)(pw + head) + vi);
         }
         if (tile == 0) {
-            // the few elements before and after the 16-byte aligned body
+            // the few elements before and after the 128-byte aligned body
             const uint32_t tail = rem & 3u;
             const uint32_t tbase = head + (n4 << 2);
             uint32_t i = len;   // none

@@ -244,7 +244,7 @@ __device__ __forceinline__ uint32_t blend_bf16_pair(const BlendWeights &w, uint3
 // slot frees up; on this memory system that sustains about a quarter more
 // bandwidth for a two-read-one-write stream than a resident grid of 256-thread
 // workgroups striding over large chunks.  Tile 0 of a chunk also takes the few
-// elements before and after the 16-byte aligned body.
+// elements before and after the 128-byte aligned body.
 __device__ __forceinline__ void blend_tile_f32(const BlendWeights &w, gcf32 pa, gcf32 pb, gf32 po, uint32_t len,
                                                uint32_t tile, uint32_t tid)
 {
@@ -258,7 +258,7 @@ __device__ __forceinline__ void blend_tile_f32(const BlendWeights &w, gcf32 pa, 
         }
         return;
     }
-    const uint32_t head = head_elems((uint64_t)pa, 4u, len);
+    const uint32_t head = head_elems((uint64_t)po, 4u, len);   // whole lines for the stream that is written
     const uint32_t rem = len - head;
     const uint32_t n4 = rem >> 2;
     const uint32_t v = tile * CF_TILE_THREADS + tid;
@@ -297,7 +297,7 @@ __device__ __forceinline__ void blend_tile_bf16(const BlendWeights &w, gcu16 pa,
         }
         return;
     }
-    const uint32_t head = head_elems((uint64_t)pa, 2u, len);
+    const uint32_t head = head_elems((uint64_t)po, 2u, len);   // whole lines for the stream that is written
     const uint32_t rem = len - head;
     const uint32_t n8 = rem >> 3;
     const uint32_t v = tile * CF_TILE_THREADS + tid;
@@ -407,16 +407,23 @@ __global__ __launch_bounds__(CF_TILE_THREADS) void cf_copy_kernel(const CfChunk 
         }
         return;
     }
-    const uint32_t head = head_elems((uint64_t)ps, 1u, nbytes);
+    const uint32_t head = head_elems((uint64_t)pd, 1u, nbytes);   // whole lines for the stream that is written
     const uint32_t rem = nbytes - head;
     const uint32_t n16 = rem >> 4;
     const uint32_t v = tile * CF_TILE_THREADS + tid;
     if (v < n16) __builtin_nontemporal_store(__builtin_nontemporal_load((gcu32x4)(ps + head) + v), (gu32x4)(pd + head) + v);
     if (tile == 0) {
-        if (tid < head) pd[tid] = ps[tid];
+        // Up to 127 bytes before the body and 15 behind it, moved as whole elements (both are
+        // multiples of the element size, and the tensors are aligned to it).
         const uint32_t tail = rem & 15u;
         const uint32_t tbase = head + (n16 << 4);
-        if (tid < tail) pd[tbase + tid] = ps[tbase + tid];
+        if (esize == 4u) {
+            if (tid < (head >> 2)) ((gu32)pd)[tid] = ((gcu32)ps)[tid];
+            if (tid < (tail >> 2)) ((gu32)(pd + tbase))[tid] = ((gcu32)(ps + tbase))[tid];
+        } else {
+            if (tid < (head >> 1)) ((gu16)pd)[tid] = ((gcu16)ps)[tid];
+            if (tid < (tail >> 1)) ((gu16)(pd + tbase))[tid] = ((gcu16)(ps + tbase))[tid];
+        }
     }
 }
 
