@@ -52,14 +52,27 @@ __device__ __forceinline__ double chunk_sqsum_f32(gcf32 p, uint32_t len, uint32_
     gcf32x4 q = (gcf32x4)(p + head);
     const uint32_t rem = len - head;
     const uint32_t n4 = rem >> 2;
-    // kUnroll loads in flight in every round, the last round included: a lane whose vector lies past the
-    // chunk's end takes zeros instead, and adding the square of zero changes no accumulator.
-    for (uint32_t base = tid; base < n4 + tid; base += kUnroll * CF_THREADS) {
+    uint32_t i = tid;
+    for (; i + (kUnroll - 1) * CF_THREADS < n4; i += kUnroll * CF_THREADS) {
+        f32x4 v[kUnroll];
+#pragma unroll
+        for (int u = 0; u < kUnroll; ++u) v[u] = __builtin_nontemporal_load(q + i + u * CF_THREADS);
+#pragma unroll
+        for (int u = 0; u < kUnroll; ++u) {
+            sq_acc(a0, v[u].x);
+            sq_acc(a1, v[u].y);
+            sq_acc(a2, v[u].z);
+            sq_acc(a3, v[u].w);
+        }
+    }
+    if (i < n4) {
+        // The last, partial round keeps its loads in flight together too: a lane whose vector lies
+        // past the chunk's end takes zeros instead, and adding the square of zero changes no accumulator.
         f32x4 v[kUnroll];
 #pragma unroll
         for (int u = 0; u < kUnroll; ++u) {
-            const uint32_t i = base + u * CF_THREADS;
-            v[u] = (i < n4) ? __builtin_nontemporal_load(q + i) : (f32x4)(0.f);
+            const uint32_t j = i + u * CF_THREADS;
+            v[u] = (j < n4) ? __builtin_nontemporal_load(q + j) : (f32x4)(0.f);
         }
 #pragma unroll
         for (int u = 0; u < kUnroll; ++u) {
@@ -91,12 +104,25 @@ __device__ __forceinline__ double chunk_sqsum_bf16(gcu16 p, uint32_t len, uint32
     gcu32x4 q = (gcu32x4)(p + head);
     const uint32_t rem = len - head;
     const uint32_t n8 = rem >> 3;
-    for (uint32_t base = tid; base < n8 + tid; base += kUnroll * CF_THREADS) {
+    uint32_t i = tid;
+    for (; i + (kUnroll - 1) * CF_THREADS < n8; i += kUnroll * CF_THREADS) {
+        u32x4 v[kUnroll];
+#pragma unroll
+        for (int u = 0; u < kUnroll; ++u) v[u] = __builtin_nontemporal_load(q + i + u * CF_THREADS);
+#pragma unroll
+        for (int u = 0; u < kUnroll; ++u) {
+            sq_acc_bf16_word(a0, a1, v[u].x);
+            sq_acc_bf16_word(a2, a3, v[u].y);
+            sq_acc_bf16_word(a0, a1, v[u].z);
+            sq_acc_bf16_word(a2, a3, v[u].w);
+        }
+    }
+    if (i < n8) {
         u32x4 v[kUnroll];
 #pragma unroll
         for (int u = 0; u < kUnroll; ++u) {
-            const uint32_t i = base + u * CF_THREADS;
-            v[u] = (i < n8) ? __builtin_nontemporal_load(q + i) : (u32x4)(0u);
+            const uint32_t j = i + u * CF_THREADS;
+            v[u] = (j < n8) ? __builtin_nontemporal_load(q + j) : (u32x4)(0u);
         }
 #pragma unroll
         for (int u = 0; u < kUnroll; ++u) {
