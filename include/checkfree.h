@@ -96,12 +96,11 @@ enum {
 };
 
 /* One contiguous tensor in device memory.  `data` must be aligned to the element
- * size; nothing more is required.  Corresponding tensors of the stages of one
- * call whose addresses agree modulo 16 (tensors from an allocator always do;
- * views into flat buffers at the same offset do) are moved 16 bytes per lane,
- * with the vector body placed on 128-byte boundaries of the written tensor, at
- * the same speed whatever the offset; others are moved element by element.
- * numel may be 0 (then data may be NULL). */
+ * size; nothing more is required.  Every kernel moves 16 bytes per lane, with
+ * the vector body placed on the 128-byte boundaries of the tensor it writes and
+ * the tensors it reads read at whatever alignment they have: views into flat
+ * buffers at odd offsets run within a few per cent of tensors that came from
+ * an allocator.  numel may be 0 (then data may be NULL). */
 typedef struct cf_tensor {
     void *data;      /* device pointer */
     uint64_t numel;  /* number of elements */

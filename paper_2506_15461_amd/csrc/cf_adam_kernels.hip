@@ -66,61 +66,47 @@ __global__ __launch_bounds__(CF_TILE_THREADS) void cf_adam_sqnorm_kernel(const C
     gf32 pv = (gf32)cv.addr;
     gf32 pw = (gf32)cw.addr;
 
+    // The vector body lies on the 128-byte boundaries of the weights; gradient and moments are
+    // read, and the moments written, at whatever alignment they have.
     double sq = 0.0;
-    const uint32_t mis = (uint32_t)(cg.addr & 15u);
-    if (mis != (uint32_t)(cm.addr & 15u) || mis != (uint32_t)(cv.addr & 15u) || mis != (uint32_t)(cw.addr & 15u)) {
-        // The four tensors sit differently inside their 16-byte lines: dword path.
-#pragma unroll
-        for (uint32_t j = 0; j < 4; ++j) {
-            const uint32_t i = tile * (4u * CF_TILE_THREADS) + j * CF_TILE_THREADS + tid;
-            if (i < len) {
-                float m = pm[i], v = pv[i], w = pw[i];
-                adam_element(p, pg[i], m, v, w, sq);
-                pm[i] = m;
-                pv[i] = v;
-                pw[i] = w;
-            }
-        }
-    } else {
-        const uint32_t head = head_elems(cw.addr, 4u, len);   // whole lines for the streams that are written
-        const uint32_t rem = len - head;
-        const uint32_t n4 = rem >> 2;
-        const uint32_t vi = tile * CF_TILE_THREADS + tid;
-        if (vi < n4) {
-            const f32x4 g = __builtin_nontemporal_load((gcf32x4)(pg + head) + vi);
-            f32x4 m = __builtin_nontemporal_load((gcf32x4)(pm + head) + vi);
-            f32x4 v = __builtin_nontemporal_load((gcf32x4)(pv + head) + vi);
-            f32x4 w = __builtin_nontemporal_load((gcf32x4)(pw + head) + vi);
-            float m0 = m.x, m1 = m.y, m2 = m.z, m3 = m.w;
-            float v0 = v.x, v1 = v.y, v2 = v.z, v3 = v.w;
-            float w0 = w.x, w1 = w.y, w2 = w.z, w3 = w.w;
-            double s0 = 0.0, s1 = 0.0, s2 = 0.0, s3 = 0.0;
-            adam_element(p, g.x, m0, v0, w0, s0);
-            adam_element(p, g.y, m1, v1, w1, s1);
-            adam_element(p, g.z, m2, v2, w2, s2);
-            adam_element(p, g.w, m3, v3, w3, s3);
-            sq = (s0 + s1) + (s2 + s3);
-            m.x = m0, m.y = m1, m.z = m2, m.w = m3;
-            v.x = v0, v.y = v1, v.z = v2, v.w = v3;
-            w.x = w0, w.y = w1, w.z = w2, w.w = w3;
-            __builtin_nontemporal_store(m, (gf32x4)(pm + head) + vi);
-            __builtin_nontemporal_store(v, (gf32x4)(pv + head) + vi);
-            __builtin_nontemporal_store(w, (gf32x4)(pw + head) + vi);
-        }
-        if (tile == 0) {
-            // the few elements before and after the 128-byte aligned body
-            const uint32_t tail = rem & 3u;
-            const uint32_t tbase = head + (n4 << 2);
-            uint32_t i = len;   // none
-            if (tid < head) i = tid;
-            else if (tid - head < tail) i = tbase + (tid - head);
-            if (i < len) {
-                float m = pm[i], v = pv[i], w = pw[i];
-                adam_element(p, pg[i], m, v, w, sq);
-                pm[i] = m;
-                pv[i] = v;
-                pw[i] = w;
-            }
+    const uint32_t head = head_elems(cw.addr, 4u, len);   // whole lines for the streams that are written
+    const uint32_t rem = len - head;
+    const uint32_t n4 = rem >> 2;
+    const uint32_t vi = tile * CF_TILE_THREADS + tid;
+    if (vi < n4) {
+        const f32x4 g = __builtin_nontemporal_load((gcf32x4_e4)(pg + head) + vi);
+        f32x4 m = __builtin_nontemporal_load((gcf32x4_e4)(pm + head) + vi);
+        f32x4 v = __builtin_nontemporal_load((gcf32x4_e4)(pv + head) + vi);
+        f32x4 w = __builtin_nontemporal_load((gcf32x4)(pw + head) + vi);
+        float m0 = m.x, m1 = m.y, m2 = m.z, m3 = m.w;
+        float v0 = v.x, v1 = v.y, v2 = v.z, v3 = v.w;
+        float w0 = w.x, w1 = w.y, w2 = w.z, w3 = w.w;
+        double s0 = 0.0, s1 = 0.0, s2 = 0.0, s3 = 0.0;
+        adam_element(p, g.x, m0, v0, w0, s0);
+        adam_element(p, g.y, m1, v1, w1, s1);
+        adam_element(p, g.z, m2, v2, w2, s2);
+        adam_element(p, g.w, m3, v3, w3, s3);
+        sq = (s0 + s1) + (s2 + s3);
+        m.x = m0, m.y = m1, m.z = m2, m.w = m3;
+        v.x = v0, v.y = v1, v.z = v2, v.w = v3;
+        w.x = w0, w.y = w1, w.z = w2, w.w = w3;
+        __builtin_nontemporal_store(m, (gf32x4_e4)(pm + head) + vi);
+        __builtin_nontemporal_store(v, (gf32x4_e4)(pv + head) + vi);
+        __builtin_nontemporal_store(w, (gf32x4)(pw + head) + vi);
+    }
+    if (tile == 0) {
+        // the few elements before and after the 128-byte aligned body
+        const uint32_t tail = rem & 3u;
+        const uint32_t tbase = head + (n4 << 2);
+        uint32_t i = len;   // none
+        if (tid < head) i = tid;
+        else if (tid - head < tail) i = tbase + (tid - head);
+        if (i < len) {
+            float m = pm[i], v = pv[i], w = pw[i];
+            adam_element(p, pg[i], m, v, w, sq);
+            pm[i] = m;
+            pv[i] = v;
+            pw[i] = w;
         }
     }
     const double t = wave_sum(sq);

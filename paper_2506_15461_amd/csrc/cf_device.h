@@ -28,6 +28,20 @@ typedef CF_GLOBAL uint32_t *gu32;
 typedef CF_GLOBAL const unsigned char *gcu8;
 typedef CF_GLOBAL unsigned char *gu8;
 
+// Sixteen-byte vectors that are only known to be aligned to their element (4 or
+// 2 bytes).  The vector body of a kernel is laid on the 128-byte boundaries of
+// the tensor it writes; the tensors it reads may sit differently inside their
+// lines, and are then read with the same one-instruction 16-byte loads at
+// whatever alignment they have (global memory accesses need no more than that
+// on this platform).
+typedef f32x4 f32x4_e4 __attribute__((aligned(4)));
+typedef u32x4 u32x4_e4 __attribute__((aligned(4)));
+typedef u32x4 u32x4_e2 __attribute__((aligned(2)));
+typedef CF_GLOBAL const f32x4_e4 *gcf32x4_e4;
+typedef CF_GLOBAL f32x4_e4 *gf32x4_e4;
+typedef CF_GLOBAL const u32x4_e4 *gcu32x4_e4;
+typedef CF_GLOBAL const u32x4_e2 *gcu32x4_e2;
+
 constexpr uint32_t kFlagDegenerateOmega = 1u;
 constexpr uint32_t kFlagNonfiniteOmega = 2u;
 constexpr uint32_t kDtypeF32 = 0u;

@@ -270,27 +270,19 @@ __device__ __forceinline__ uint32_t blend_bf16_pair(const BlendWeights &w, uint3
 // slot frees up; on this memory system that sustains about a quarter more
 // bandwidth for a two-read-one-write stream than a resident grid of 256-thread
 // workgroups striding over large chunks.  Tile 0 of a chunk also takes the few
-// elements before and after the 128-byte aligned body.
+// elements before and after the body.  The body is laid on the 128-byte
+// boundaries of the written tensor; the two tensors that are read may sit
+// differently inside their lines and are read at whatever alignment they have.
 __device__ __forceinline__ void blend_tile_f32(const BlendWeights &w, gcf32 pa, gcf32 pb, gf32 po, uint32_t len,
                                                uint32_t tile, uint32_t tid)
 {
-    const uint32_t mis = (uint32_t)((uint64_t)pa & 15u);
-    if (mis != (uint32_t)((uint64_t)pb & 15u) || mis != (uint32_t)((uint64_t)po & 15u)) {
-        // The three tensors sit differently inside their 16-byte lines: dword path.
-#pragma unroll
-        for (uint32_t j = 0; j < 4; ++j) {
-            const uint32_t i = tile * (4u * CF_TILE_THREADS) + j * CF_TILE_THREADS + tid;
-            if (i < len) po[i] = blend_to_f32(w, pa[i], pb[i]);
-        }
-        return;
-    }
     const uint32_t head = head_elems((uint64_t)po, 4u, len);   // whole lines for the stream that is written
     const uint32_t rem = len - head;
     const uint32_t n4 = rem >> 2;
     const uint32_t v = tile * CF_TILE_THREADS + tid;
     if (v < n4) {
-        const f32x4 a = __builtin_nontemporal_load((gcf32x4)(pa + head) + v);
-        const f32x4 b = __builtin_nontemporal_load((gcf32x4)(pb + head) + v);
+        const f32x4 a = __builtin_nontemporal_load((gcf32x4_e4)(pa + head) + v);
+        const f32x4 b = __builtin_nontemporal_load((gcf32x4_e4)(pb + head) + v);
         f32x4 o;
         o.x = blend_to_f32(w, a.x, b.x);
         o.y = blend_to_f32(w, a.y, b.y);
@@ -314,22 +306,13 @@ __device__ __forceinline__ uint16_t blend_to_bf16(const BlendWeights &w, uint16_
 __device__ __forceinline__ void blend_tile_bf16(const BlendWeights &w, gcu16 pa, gcu16 pb, gu16 po, uint32_t len,
                                                 uint32_t tile, uint32_t tid)
 {
-    const uint32_t mis = (uint32_t)((uint64_t)pa & 15u);
-    if (mis != (uint32_t)((uint64_t)pb & 15u) || mis != (uint32_t)((uint64_t)po & 15u)) {
-#pragma unroll
-        for (uint32_t j = 0; j < 8; ++j) {
-            const uint32_t i = tile * (8u * CF_TILE_THREADS) + j * CF_TILE_THREADS + tid;
-            if (i < len) po[i] = blend_to_bf16(w, pa[i], pb[i]);
-        }
-        return;
-    }
     const uint32_t head = head_elems((uint64_t)po, 2u, len);   // whole lines for the stream that is written
     const uint32_t rem = len - head;
     const uint32_t n8 = rem >> 3;
     const uint32_t v = tile * CF_TILE_THREADS + tid;
     if (v < n8) {
-        const u32x4 a = __builtin_nontemporal_load((gcu32x4)(pa + head) + v);
-        const u32x4 b = __builtin_nontemporal_load((gcu32x4)(pb + head) + v);
+        const u32x4 a = __builtin_nontemporal_load((gcu32x4_e2)(pa + head) + v);
+        const u32x4 b = __builtin_nontemporal_load((gcu32x4_e2)(pb + head) + v);
         u32x4 o;
         o.x = blend_bf16_pair(w, a.x, b.x);
         o.y = blend_bf16_pair(w, a.y, b.y);
@@ -412,32 +395,16 @@ __global__ __launch_bounds__(CF_TILE_THREADS) void cf_copy_kernel(const CfChunk 
     const CfChunk cs = src[c];
     gcu8 ps = (gcu8)cs.addr;
     gu8 pd = (gu8)cd.addr;
-    if (((uint64_t)ps & 15u) != ((uint64_t)pd & 15u)) {
-        // Different position inside a 16-byte line: move whole elements.
-        if (esize == 4u) {
-            gcu32 s4 = (gcu32)ps;
-            gu32 d4 = (gu32)pd;
-#pragma unroll
-            for (uint32_t j = 0; j < 4; ++j) {
-                const uint32_t i = tile * (4u * CF_TILE_THREADS) + j * CF_TILE_THREADS + tid;
-                if (i < cd.len) d4[i] = s4[i];
-            }
-        } else {
-            gcu16 s2 = (gcu16)ps;
-            gu16 d2 = (gu16)pd;
-#pragma unroll
-            for (uint32_t j = 0; j < 8; ++j) {
-                const uint32_t i = tile * (8u * CF_TILE_THREADS) + j * CF_TILE_THREADS + tid;
-                if (i < cd.len) d2[i] = s2[i];
-            }
-        }
-        return;
-    }
     const uint32_t head = head_elems((uint64_t)pd, 1u, nbytes);   // whole lines for the stream that is written
     const uint32_t rem = nbytes - head;
     const uint32_t n16 = rem >> 4;
     const uint32_t v = tile * CF_TILE_THREADS + tid;
-    if (v < n16) __builtin_nontemporal_store(__builtin_nontemporal_load((gcu32x4)(ps + head) + v), (gu32x4)(pd + head) + v);
+    if (v < n16) {
+        // the source may sit differently inside its lines: read at element alignment
+        const u32x4 x = (esize == 4u) ? __builtin_nontemporal_load((gcu32x4_e4)(ps + head) + v)
+                                      : __builtin_nontemporal_load((gcu32x4_e2)(ps + head) + v);
+        __builtin_nontemporal_store(x, (gu32x4)(pd + head) + v);
+    }
     if (tile == 0) {
         // Up to 127 bytes before the body and 15 behind it, moved as whole elements (both are
         // multiples of the element size, and the tensors are aligned to it).
