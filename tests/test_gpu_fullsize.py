@@ -108,3 +108,61 @@ def test_one_tensor_beyond_four_gib(ctx, dev):
     cf.cf_copy_stage(ctx, cf.Stage(ctx, [b]), sa)
     torch.cuda.synchronize()
     assert torch.equal(a.view(torch.int32), b.view(torch.int32))
+
+
+def test_norm_bits_do_not_depend_on_the_launch_shape_at_full_size(dev):
+    """The two neighbours' gradients of workload 3 (1.6 GB): the automatic choice walks the chunk list with 512
+    resident workgroups at this size; one workgroup per chunk, other caps, repeated calls and the entry point
+    that works in the library's static array must all give the same bits, per stage and per tensor."""
+    wl = workloads.make_workload(3, device=dev)
+    refs = [oracle.stage_grad_sqnorm(np_stage(wl.grads[s]), ORACLE_THREADS) for s in (0, 2)]
+    seen, seen_tensors = set(), set()
+    for tuning in ({}, {"sqnorm_blocks_per_cu": 65}, {"sqnorm_blocks_per_cu": 1}, {"sqnorm_blocks_per_cu": 5}):
+        c = cf.Context(0, **tuning)
+        handles = [cf.Stage(c, wl.grads[0]), cf.Stage(c, wl.grads[2])]
+        for rep in range(3):
+            seen.add(cf.cf_stage_grad_sqnorm(c, handles).cpu().numpy().tobytes())
+        om, per = cf.cf_stage_grad_sqnorm_per_tensor(c, handles[0])
+        seen_tensors.add(per.cpu().numpy().tobytes())
+        one = torch.zeros(1, dtype=torch.float64, device=dev)
+        cf.cf_stage_grad_sqnorm_static(c, wl.grads[2], one)
+        torch.cuda.synchronize()
+        got = np.frombuffer(next(iter(seen)), dtype=np.float64)
+        assert om.item() == got[0] and one.item() == got[1]
+        assert c.read_flags() == 0
+    assert len(seen) == 1 and len(seen_tensors) == 1
+    got = np.frombuffer(next(iter(seen)), dtype=np.float64)
+    for k in range(2):
+        assert abs(got[k] - refs[k]) <= 1e-12 * refs[k]
+    per = np.frombuffer(next(iter(seen_tensors)), dtype=np.float64)
+    want = oracle.tensor_grad_sqnorms(np_stage(wl.grads[0]))
+    assert len(per) == 36
+    for t in range(36):
+        assert abs(per[t] - want[t]) <= 1e-12 * want[t], t
+
+
+def test_replica_refresh_in_slices_at_full_size(ctx, dev):
+    """Embedding and de-embedding of workload 4 (2 x 262 MB) refreshed in 7 uneven slices issued on two
+    streams: bit for bit the whole copy, and a slice touches nothing outside its chunks."""
+    wl = workloads.make_workload(4, device=dev, with_grads=False)
+    src = list(wl.extra[:2])
+    dst = [torch.full_like(t, float("nan")) for t in src]
+    s, d = cf.Stage(ctx, src), cf.Stage(ctx, dst)
+    n = s.num_chunks
+    assert n == 4000
+    cf.cf_copy_stage_range(ctx, s, d, 1000, 500)
+    torch.cuda.synchronize()
+    flat = dst[0].view(-1)
+    per = 32768                                              # elements per chunk; E has 2000 chunks
+    assert torch.equal(flat[1000 * per:1500 * per].view(torch.int32), src[0].view(-1)[1000 * per:1500 * per].view(torch.int32))
+    assert torch.isnan(flat[:1000 * per]).all() and torch.isnan(flat[1500 * per:]).all() and torch.isnan(dst[1]).all()
+    cuts = [0, 1, 777, 1000, 1500, 2000, 2001, n]
+    streams = [torch.cuda.Stream(), torch.cuda.Stream()]
+    torch.cuda.synchronize()
+    for k in range(len(cuts) - 1):
+        cf.cf_copy_stage_range(ctx, s, d, cuts[k], cuts[k + 1] - cuts[k], streams[k % 2])
+    torch.cuda.synchronize()
+    for a, b in zip(src, dst):
+        assert torch.equal(a.view(torch.int32), b.view(torch.int32))
+    want = oracle.copy_stage([workloads.to_numpy(src[1])], ORACLE_THREADS)[0]
+    assert workloads.to_numpy(dst[1]).tobytes() == want.tobytes()
