@@ -324,10 +324,13 @@ def main():
     if not args.no_per_config and args.config == 3 and not args.shape:
         run.close()
         per = {}
+        # (steps, warm-up steps): about 30 ms of warm-up each, so that the clocks have settled after the
+        # host-bound construction of the workload, and at least 50 ms timed
+        plan = {1: (1000, 600), 2: (500, 300), 4: (150, 80), 5: (60, 30)}
         for c in (1, 2, 4, 5):
-            steps = 200 if c in (1, 2) else 60
+            steps, warm = plan[c]
             r = Runner(c, args, ctx, cf, torch, workloads)
-            ms, kms, _ = r.time_steps(steps, 10)
+            ms, kms, _ = r.time_steps(steps, warm)
             entry = {"workload": r.spec.name, "ms_per_step": round(ms, 5), "GBps": round(r.step_bytes / ms / 1e6, 1),
                      "frac_of_hbm_peak": round(r.step_bytes / ms / 1e6 / HBM_PEAK_GBPS, 4),
                      "algorithmic_bytes_per_step": int(r.step_bytes), "steps": steps, "buffer_sets_rotated": r.n_sets,
