@@ -42,7 +42,7 @@ HBM_PEAK_GBPS = 8000.0          # MI355X HBM3E, vendor figure
 # on: reported as null once those have changed.
 TRAFFIC_PROFILE = "profiles/cf_kernels_hbm_traffic_pmc.md"
 TRAFFIC_KERNEL_SHA256 = "59a8d51eea80516172c4f19bf896e3b750e8068b0d9fde436b682610e51e42b2"
-TRAFFIC_BYTES_PER_LAUNCH = {(3, "cf_blend_kernel"): 2471167000}
+TRAFFIC_BYTES_PER_LAUNCH = {(3, "cf_blend_kernel"): 2471143000}
 
 
 def kernel_sources_sha256():

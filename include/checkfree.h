@@ -113,9 +113,9 @@ typedef struct cf_tuning {
     uint32_t chunk_bytes;          /* bytes per work chunk: a power of two, 4 KiB .. 4 MiB (default 128 KiB);
                                       results of the norm differ between chunk sizes only in the last bits */
     uint32_t sqnorm_blocks_per_cu; /* grid of the norm's first pass: 1..64 = at most that many workgroups per
-                                      compute unit; 65 = one workgroup per chunk; default 0 = chosen by the
-                                      size of the launch (one per chunk below 512 MiB of gradients, two per
-                                      compute unit from there on).  Never changes a result bit. */
+                                      compute unit, every workgroup with the same number of chunks; 65 = one
+                                      workgroup per chunk; default 0 = 2 per compute unit (the measured best
+                                      from 100 MB to several GB).  Never changes a result bit. */
     uint32_t reserved0;
     uint32_t reserved1;
 } cf_tuning;

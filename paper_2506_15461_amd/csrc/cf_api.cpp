@@ -19,10 +19,9 @@ namespace {
 constexpr uint32_t kDefaultChunkBytes = 128u << 10;   // 128 tiles of 1 KiB
 constexpr uint32_t kMinChunkBytes = 4096;
 constexpr uint32_t kMaxChunkBytes = 4u << 20;
-constexpr uint32_t kDefaultSqnormBlocksPerCu = 0;     // 0: chosen by the size of the launch
+constexpr uint32_t kDefaultSqnormBlocksPerCu = 0;     // 0: the measured best (kCappedGridPerCu)
 constexpr uint32_t kOnePerChunk = 65;                 // tuning value that forces one workgroup per chunk
 constexpr uint32_t kCappedGridPerCu = 2;
-constexpr uint64_t kCappedGridFromBytes = 512ull << 20;
 constexpr uint64_t kMaxChunksPerStage = 1ull << 31;
 constexpr uint64_t kMaxGrid = (1ull << 31) - 1;
 constexpr size_t kCtxWordBytes = CF_CTX_WORDS * sizeof(uint32_t);
@@ -260,16 +259,22 @@ hipError_t enqueue_table(const cf_ctx *ctx, const cf_tensor *tensors, uint32_t n
 }
 
 // Grid of the norm's first pass.  The partials are per chunk, so the result does not depend on this
-// choice; only the speed does.  Measured on this chip: up to a few thousand chunks one workgroup per
-// chunk is as fast or faster (the launch is over before a capped grid has paid for itself); from about
-// half a GiB of gradients on, 512 resident workgroups walking the chunk list are 1-3 % faster than
-// thousands of short-lived ones.
+// choice; only the speed does.  Measured on this chip (cold gradients of 113 MB, 411 MB, 822 MB and
+// 1.6 GB): two resident workgroups per compute unit walking the chunk list, every workgroup with the
+// same number of chunks, are 1.5-3.5 % faster than one short-lived workgroup per chunk at every size;
+// three or four per compute unit are not.
 uint32_t sqnorm_grid(const cf_ctx *ctx, uint32_t n_chunks)
 {
     uint64_t g = n_chunks;
     uint32_t per_cu = ctx->tuning.sqnorm_blocks_per_cu;
-    if (per_cu == 0 && (uint64_t)n_chunks * ctx->tuning.chunk_bytes >= kCappedGridFromBytes) per_cu = kCappedGridPerCu;
-    if (per_cu && per_cu != kOnePerChunk) g = std::min<uint64_t>(g, (uint64_t)ctx->num_cu * per_cu);
+    if (per_cu == 0) per_cu = kCappedGridPerCu;
+    if (per_cu && per_cu != kOnePerChunk && g > (uint64_t)ctx->num_cu * per_cu) {
+        // Every workgroup of the capped grid gets the same number of chunks (or one fewer): with
+        // `rounds` passes over the grid, the smallest grid that needs no more passes.
+        const uint64_t cap = (uint64_t)ctx->num_cu * per_cu;
+        const uint64_t rounds = (n_chunks + cap - 1) / cap;
+        g = (n_chunks + rounds - 1) / rounds;
+    }
     return (uint32_t)std::max<uint64_t>(g, 1);
 }
 
