@@ -56,8 +56,7 @@ __global__ __launch_bounds__(CF_TILE_THREADS) void cf_adam_sqnorm_kernel(const C
     const uint32_t c = blockIdx.x >> tile_shift;
     const uint32_t tile = blockIdx.x & ((1u << tile_shift) - 1u);
     const CfChunk cg = grads[c];
-    const uint32_t len = cg.len;
-    if (tile != 0 && (uint64_t)tile * CF_TILE_BYTES >= (uint64_t)len * 4u) return;
+    const uint32_t len = cg.len;   // a tile past the end of a short chunk finds no vector below and adds 0
     const CfChunk cw = weights[c];
     const CfChunk cm = exp_avg[c];
     const CfChunk cv = exp_avg_sq[c];

@@ -263,6 +263,35 @@ __device__ __forceinline__ uint32_t blend_bf16_pair(const BlendWeights &w, uint3
     return lo | (hi << 16);
 }
 
+// The two omegas as they arrive (device memory or host-given) and what the
+// blend needs of them.  make_weights() holds the norm-to-weight scaling: the
+// usable-pair rule, the common power of two, the one binary64 division.
+__device__ __forceinline__ BlendWeights make_weights(double wp, double wn, uint32_t *words, bool reporter)
+{
+    BlendWeights w;
+    w.wp = wp;
+    w.wn = wn;
+    double den = w.wp + w.wn;
+    // Usable pair: both finite and non-negative, sum a positive normal number.
+    const bool usable = (w.wp - w.wp == 0.0) && (w.wn - w.wn == 0.0) && w.wp >= 0.0 && w.wn >= 0.0 &&
+                        (den - den == 0.0) && den >= 2.2250738585072014e-308;
+    if (!usable) {
+        w.wp = 1.0;
+        w.wn = 1.0;
+        den = 2.0;
+        if (reporter) atomicOr(&words[CF_WORD_FLAGS], kFlagDegenerateOmega);
+    }
+    // The equation does not change when both weights are multiplied by one
+    // number: scale them by the power of two that brings their sum into [1, 2)
+    // (exact), so that no product weight x value leaves the binary64 range
+    // whatever the magnitude of the omegas.
+    const int scale = 1023 - (int)((uint64_t)__double_as_longlong(den) >> 52);
+    w.wp = __builtin_ldexp(w.wp, scale);
+    w.wn = __builtin_ldexp(w.wn, scale);
+    w.rcp = 1.0 / (w.wp + w.wn);
+    return w;
+}
+
 // One single-wavefront workgroup blends one *tile*: 64 sixteen-byte vectors of
 // each of the three streams, one vector per lane.  Workgroups are dispatched in
 // tile order, so at any moment the chip reads two narrow moving windows and
@@ -273,16 +302,36 @@ __device__ __forceinline__ uint32_t blend_bf16_pair(const BlendWeights &w, uint3
 // elements before and after the body.  The body is laid on the 128-byte
 // boundaries of the written tensor; the two tensors that are read may sit
 // differently inside their lines and are read at whatever alignment they have.
-__device__ __forceinline__ void blend_tile_f32(const BlendWeights &w, gcf32 pa, gcf32 pb, gf32 po, uint32_t len,
-                                               uint32_t tile, uint32_t tid)
+// The tile's loads are issued first and the weights are derived while they are
+// in flight: a wavefront lives for one load-compute-store round, so the
+// division must not stand between its start and its loads.
+__device__ __forceinline__ void blend_tile_f32(double wp, double wn, uint32_t *words, bool reporter, gcf32 pa, gcf32 pb,
+                                               gf32 po, uint32_t len, uint32_t tile, uint32_t tid)
 {
     const uint32_t head = head_elems((uint64_t)po, 4u, len);   // whole lines for the stream that is written
     const uint32_t rem = len - head;
     const uint32_t n4 = rem >> 2;
     const uint32_t v = tile * CF_TILE_THREADS + tid;
+    const uint32_t tail = rem & 3u;
+    const uint32_t tbase = head + (n4 << 2);
+    // an extra element of tile 0: lane t < head takes element t, lane head <= t < head + tail a tail element
+    uint32_t extra = len;
+    if (tile == 0) {
+        if (tid < head) extra = tid;
+        else if (tid - head < tail) extra = tbase + (tid - head);
+    }
+    f32x4 a = (f32x4)(0.f), b = (f32x4)(0.f);
+    float ea = 0.f, eb = 0.f;
     if (v < n4) {
-        const f32x4 a = __builtin_nontemporal_load((gcf32x4_e4)(pa + head) + v);
-        const f32x4 b = __builtin_nontemporal_load((gcf32x4_e4)(pb + head) + v);
+        a = __builtin_nontemporal_load((gcf32x4_e4)(pa + head) + v);
+        b = __builtin_nontemporal_load((gcf32x4_e4)(pb + head) + v);
+    }
+    if (extra < len) {
+        ea = pa[extra];
+        eb = pb[extra];
+    }
+    const BlendWeights w = make_weights(wp, wn, words, reporter);
+    if (v < n4) {
         f32x4 o;
         o.x = blend_to_f32(w, a.x, b.x);
         o.y = blend_to_f32(w, a.y, b.y);
@@ -290,12 +339,7 @@ __device__ __forceinline__ void blend_tile_f32(const BlendWeights &w, gcf32 pa, 
         o.w = blend_to_f32(w, a.w, b.w);
         __builtin_nontemporal_store(o, (gf32x4)(po + head) + v);
     }
-    if (tile == 0) {
-        if (tid < head) po[tid] = blend_to_f32(w, pa[tid], pb[tid]);
-        const uint32_t tail = rem & 3u;
-        const uint32_t tbase = head + (n4 << 2);
-        if (tid < tail) po[tbase + tid] = blend_to_f32(w, pa[tbase + tid], pb[tbase + tid]);
-    }
+    if (extra < len) po[extra] = blend_to_f32(w, ea, eb);
 }
 
 __device__ __forceinline__ uint16_t blend_to_bf16(const BlendWeights &w, uint16_t a, uint16_t b)
@@ -303,16 +347,34 @@ __device__ __forceinline__ uint16_t blend_to_bf16(const BlendWeights &w, uint16_
     return (uint16_t)f64_to_bf16_bits(blend_f64(w, bf16_bits_to_f64(a), bf16_bits_to_f64(b)));
 }
 
-__device__ __forceinline__ void blend_tile_bf16(const BlendWeights &w, gcu16 pa, gcu16 pb, gu16 po, uint32_t len,
-                                                uint32_t tile, uint32_t tid)
+__device__ __forceinline__ void blend_tile_bf16(double wp, double wn, uint32_t *words, bool reporter, gcu16 pa, gcu16 pb,
+                                                gu16 po, uint32_t len, uint32_t tile, uint32_t tid)
 {
     const uint32_t head = head_elems((uint64_t)po, 2u, len);   // whole lines for the stream that is written
     const uint32_t rem = len - head;
     const uint32_t n8 = rem >> 3;
     const uint32_t v = tile * CF_TILE_THREADS + tid;
+    const uint32_t tail = rem & 7u;
+    const uint32_t tbase = head + (n8 << 3);
+    // extra elements of tile 0: up to 63 before the body (lane t takes element t) and up to 7 behind it
+    const bool has_head = tile == 0 && tid < head;
+    const bool has_tail = tile == 0 && tid < tail;
+    u32x4 a = (u32x4)(0u), b = (u32x4)(0u);
+    uint16_t ha = 0, hb = 0, ta = 0, tb = 0;
     if (v < n8) {
-        const u32x4 a = __builtin_nontemporal_load((gcu32x4_e2)(pa + head) + v);
-        const u32x4 b = __builtin_nontemporal_load((gcu32x4_e2)(pb + head) + v);
+        a = __builtin_nontemporal_load((gcu32x4_e2)(pa + head) + v);
+        b = __builtin_nontemporal_load((gcu32x4_e2)(pb + head) + v);
+    }
+    if (has_head) {
+        ha = pa[tid];
+        hb = pb[tid];
+    }
+    if (has_tail) {
+        ta = pa[tbase + tid];
+        tb = pb[tbase + tid];
+    }
+    const BlendWeights w = make_weights(wp, wn, words, reporter);
+    if (v < n8) {
         u32x4 o;
         o.x = blend_bf16_pair(w, a.x, b.x);
         o.y = blend_bf16_pair(w, a.y, b.y);
@@ -320,12 +382,8 @@ __device__ __forceinline__ void blend_tile_bf16(const BlendWeights &w, gcu16 pa,
         o.w = blend_bf16_pair(w, a.w, b.w);
         __builtin_nontemporal_store(o, (gu32x4)(po + head) + v);
     }
-    if (tile == 0) {
-        if (tid < head) po[tid] = blend_to_bf16(w, pa[tid], pb[tid]);
-        const uint32_t tail = rem & 7u;
-        const uint32_t tbase = head + (n8 << 3);
-        if (tid < tail) po[tbase + tid] = blend_to_bf16(w, pa[tbase + tid], pb[tbase + tid]);
-    }
+    if (has_head) po[tid] = blend_to_bf16(w, ha, hb);
+    if (has_tail) po[tbase + tid] = blend_to_bf16(w, ta, tb);
 }
 
 // Workgroup index -> (chunk, tile of the chunk).  A chunk holds at most
@@ -345,37 +403,20 @@ __global__ __launch_bounds__(CF_TILE_THREADS) void cf_blend_kernel(const CfChunk
     const uint32_t tid = threadIdx.x;
     const uint32_t c = blockIdx.x >> tile_shift;
     const uint32_t tile = blockIdx.x & ((1u << tile_shift) - 1u);
+    // Everything the wavefront needs from memory before its tile is asked for at once: the three
+    // chunk entries and the two omegas are independent loads.
     const CfChunk co = lost[c];
-    if (tile != 0 && (uint64_t)tile * CF_TILE_BYTES >= (uint64_t)co.len * (co.dtype == kDtypeF32 ? 4u : 2u)) return;
     const CfChunk ca = prev[c];
     const CfChunk cb = next[c];
-
-    BlendWeights w;
-    w.wp = d_omega_prev ? *d_omega_prev : h_omega_prev;
-    w.wn = d_omega_next ? *d_omega_next : h_omega_next;
-    double den = w.wp + w.wn;
-    // Usable pair: both finite and non-negative, sum a positive normal number.
-    const bool usable = (w.wp - w.wp == 0.0) && (w.wn - w.wn == 0.0) && w.wp >= 0.0 && w.wn >= 0.0 &&
-                        (den - den == 0.0) && den >= 2.2250738585072014e-308;
-    if (!usable) {
-        w.wp = 1.0;
-        w.wn = 1.0;
-        den = 2.0;
-        if (blockIdx.x == 0 && tid == 0) atomicOr(&words[CF_WORD_FLAGS], kFlagDegenerateOmega);
-    }
-    // The equation does not change when both weights are multiplied by one
-    // number: scale them by the power of two that brings their sum into [1, 2)
-    // (exact), so that no product weight x value leaves the binary64 range
-    // whatever the magnitude of the omegas.
-    const int scale = 1023 - (int)((uint64_t)__double_as_longlong(den) >> 52);
-    w.wp = __builtin_ldexp(w.wp, scale);
-    w.wn = __builtin_ldexp(w.wn, scale);
-    w.rcp = 1.0 / (w.wp + w.wn);
-
+    const double wp = d_omega_prev ? *d_omega_prev : h_omega_prev;
+    const double wn = d_omega_next ? *d_omega_next : h_omega_next;
+    // A tile past the end of a short chunk finds no vector of its own below and does nothing; it is
+    // not sent home earlier, since a branch here would hold the address loads back behind it.
+    const bool reporter = blockIdx.x == 0 && tid == 0;
     if (co.dtype == kDtypeF32)
-        blend_tile_f32(w, (gcf32)ca.addr, (gcf32)cb.addr, (gf32)co.addr, co.len, tile, tid);
+        blend_tile_f32(wp, wn, words, reporter, (gcf32)ca.addr, (gcf32)cb.addr, (gf32)co.addr, co.len, tile, tid);
     else
-        blend_tile_bf16(w, (gcu16)ca.addr, (gcu16)cb.addr, (gu16)co.addr, co.len, tile, tid);
+        blend_tile_bf16(wp, wn, words, reporter, (gcu16)ca.addr, (gcu16)cb.addr, (gu16)co.addr, co.len, tile, tid);
 }
 
 // ---------------------------------------------------------------------------
@@ -389,10 +430,9 @@ __global__ __launch_bounds__(CF_TILE_THREADS) void cf_copy_kernel(const CfChunk 
     const uint32_t c = first_chunk + (blockIdx.x >> tile_shift);
     const uint32_t tile = blockIdx.x & ((1u << tile_shift) - 1u);
     const CfChunk cd = dst[c];
-    const uint32_t esize = (cd.dtype == kDtypeF32) ? 4u : 2u;
-    const uint32_t nbytes = cd.len * esize;
-    if (tile != 0 && tile * CF_TILE_BYTES >= nbytes) return;
     const CfChunk cs = src[c];
+    const uint32_t esize = (cd.dtype == kDtypeF32) ? 4u : 2u;
+    const uint32_t nbytes = cd.len * esize;   // a tile past the end of a short chunk finds no vector below
     gcu8 ps = (gcu8)cs.addr;
     gu8 pd = (gu8)cd.addr;
     const uint32_t head = head_elems((uint64_t)pd, 1u, nbytes);   // whole lines for the stream that is written
