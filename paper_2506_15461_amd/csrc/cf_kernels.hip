@@ -387,10 +387,11 @@ __device__ __forceinline__ void blend_tile_bf16(double wp, double wn, uint32_t *
 }
 
 // Workgroup index -> (chunk, tile of the chunk).  A chunk holds at most
-// 2^tile_shift tiles; a workgroup whose tile lies past the chunk's end retires
-// at once.  The norm-to-weight scaling is the kernel's prologue: every
-// workgroup reads the two binary64 omegas from device memory and derives
-// identical weights (the division overlaps the tile's loads).
+// 2^tile_shift tiles; a workgroup whose tile lies past the chunk's end finds
+// no vector of its own and does nothing.  The norm-to-weight scaling belongs
+// to this kernel: every workgroup reads the two binary64 omegas from device
+// memory and derives identical weights (make_weights, called by the tile
+// functions once their loads are out).
 //
 // The omegas come from device memory (d_omega_* non-null: the norms never visit
 // the host) or, for the ablation variants with explicit weights, by value.
