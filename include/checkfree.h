@@ -418,6 +418,50 @@ CF_API cf_status cf_check_stage_pair(const cf_tensor *in, uint32_t num_in, const
 #define CF_RECOVERY_LR_FACTOR 1.1
 CF_API double cf_recovered_learning_rate(double learning_rate);
 
+/* How one lost stage is rebuilt, and from which live stages (0-based indices
+ * into the pipeline's stages, the embedding and de-embedding layers not
+ * counted). */
+enum {
+    CF_RECOVER_WEIGHTED_AVG = 0,  /* cf_recover_stage_weighted_avg(prev, next, their omegas) */
+    CF_RECOVER_COPY = 1           /* cf_copy_stage(prev); next == prev */
+};
+
+typedef struct cf_recovery_step {
+    uint32_t lost;   /* the stage to rebuild */
+    int32_t kind;    /* CF_RECOVER_WEIGHTED_AVG or CF_RECOVER_COPY */
+    uint32_t prev;   /* source stage(s) */
+    uint32_t next;
+} cf_recovery_step;
+
+/* Which operation restores each of the `n_lost` stages in `lost` (HOST array,
+ * any order, no repeats) of a pipeline of `num_stages` stages; steps[k] answers
+ * lost[k] (HOST array of n_lost entries, written only on CF_OK).
+ *   - An intermediate stage i is the weighted average of stages i-1 and i+1
+ *     (Algorithm 1: it receives W_{i-1}, omega_{i-1}, W_{i+1}, omega_{i+1}).
+ *   - The first and the last stage have a single neighbour.  Plain CheckFree
+ *     (checkfree_plus == 0) cannot rebuild them: CF_ERR_VALUE.  CheckFree+
+ *     (section "CheckFree+: First and Last Stage Recovery") copies the second
+ *     stage into the first and the second to last into the last, which the
+ *     swapped execution order has trained to stand in for them.
+ *   - A source stage must be alive: two neighbouring stages lost together
+ *     cannot be rebuilt by either method (the paper's comparison table and its
+ *     limitations paragraph): CF_ERR_VALUE.
+ * CF_ERR_LIMIT: a stage index >= num_stages, a repeated index, or fewer than 3
+ * stages (2 for a copy).  n_lost == 0 is CF_OK.  Pure host logic. */
+CF_API cf_status cf_plan_recovery(uint32_t num_stages, const uint32_t *lost, uint32_t n_lost, int checkfree_plus,
+                                  cf_recovery_step *steps);
+
+/* CheckFree+ execution order of the stages for one microbatch (same section):
+ * half of the microbatches run the stages in their standard order, the other
+ * half with the first two stages exchanged and the last two exchanged, so that
+ * the second stage learns the first one's role and the second to last the
+ * last one's.  order[p] (HOST array of num_stages entries) is the stage that
+ * runs at position p.  The paper does not say which half is which: here the
+ * even-numbered microbatches keep the standard order and the odd-numbered ones
+ * are exchanged.  The two exchanged pairs must be distinct: num_stages >= 4,
+ * else CF_ERR_LIMIT.  Pure host logic. */
+CF_API cf_status cf_plus_stage_order(uint32_t num_stages, uint64_t microbatch, uint32_t *order);
+
 /* The tuning values in effect when `tuning` is NULL or holds zeros. */
 CF_API void cf_default_tuning(cf_tuning *out);
 

@@ -20,6 +20,8 @@ equation and Algorithm 1; section "CheckFree+: First and Last Stage Recovery"):
   copy_stage_ranges(src, dst, ranges)         slices of that copy (keeping a replica current piece by piece)
   adam_step_with_sqnorm(w, m, v, g, ...)      one Adam step of a stage (the paper's optimizer) and omega of the
                                               gradient it consumed, in the same pass
+  recovery_plan(num_stages, lost, plus)       which stages rebuild each lost stage, or why none can
+  plus_stage_order(num_stages, microbatch)    CheckFree+ order of the stages for one microbatch
 """
 import ctypes
 import os
@@ -226,3 +228,49 @@ def bf16_to_f64(bits: int) -> float:
 
 def f64_to_bf16(x: float) -> int:
     return int(_lib().cfo_f64_to_bf16(float(x)))
+
+
+def recovery_plan(num_stages: int, lost, plus: bool = False):
+    """For every lost stage (0-based; the (de)embedding layers are not stages),
+    ("average", i - 1, i + 1) or ("copy", j), or raises ValueError.
+
+    Algorithm 1 rebuilds stage i from W_{i-1} and W_{i+1}: it exists only for a
+    stage with two neighbours (section "CheckFree: Memoryless Recovery", last
+    paragraph: no second neighbour to average with at the two ends).  Section
+    "CheckFree+: First and Last Stage Recovery": the first stage is copied from
+    the second, the last from the second to last.  Both need their sources
+    alive: neighbouring stages lost together are beyond either method (the
+    comparison table's row for consecutive stages; the limitations paragraph)."""
+    lost = list(lost)
+    if len(set(lost)) != len(lost) or any(not 0 <= i < num_stages for i in lost):
+        raise IndexError("lost stages must be distinct indices below num_stages")
+    plan = []
+    for i in lost:
+        if num_stages < 2:
+            raise IndexError("a pipeline of one stage has no neighbour")
+        if 0 < i < num_stages - 1:
+            step = ("average", i - 1, i + 1)
+        elif not plus:
+            raise ValueError("CheckFree cannot rebuild the first or the last stage")
+        elif i == 0:
+            step = ("copy", 1)
+        else:
+            step = ("copy", num_stages - 2)
+        if any(src in lost for src in step[1:]):
+            raise ValueError("a neighbouring stage is lost as well")
+        plan.append(step)
+    return plan
+
+
+def plus_stage_order(num_stages: int, microbatch: int):
+    """The stage at each pipeline position for one microbatch under CheckFree+
+    (its section's two printed sequences: S_1, S_2, ..., S_{s-1}, S_s for half
+    of the microbatches and S_2, S_1, ..., S_s, S_{s-1} for the other half).
+    Which half is which is not said: even microbatches take the first
+    sequence here.  The two exchanged pairs have to be distinct."""
+    if num_stages < 4:
+        raise IndexError("the first two and the last two stages must be four different stages")
+    standard = list(range(num_stages))
+    if microbatch % 2 == 0:
+        return standard
+    return [standard[1], standard[0]] + standard[2:-2] + [standard[-1], standard[-2]]

@@ -29,6 +29,7 @@ CF_ERR_NULL, CF_ERR_SHAPE_MISMATCH, CF_ERR_DTYPE, CF_ERR_ALIGN = -1, -2, -3, -4
 CF_ERR_LIMIT, CF_ERR_HIP, CF_ERR_ALIAS, CF_ERR_CONTEXT, CF_ERR_VALUE = -5, -6, -7, -8, -9
 CF_F32, CF_BF16 = 0, 1
 CF_FLAG_DEGENERATE_OMEGA, CF_FLAG_NONFINITE_OMEGA = 1, 2
+CF_RECOVER_WEIGHTED_AVG, CF_RECOVER_COPY = 0, 1
 
 # Every symbol include/checkfree.h declares.
 EXPORTS = (
@@ -41,6 +42,7 @@ EXPORTS = (
     "cf_workspace_bytes", "cf_ctx_create_in", "cf_stage_table_bytes", "cf_stage_create_in",
     "cf_copy_stage_range", "cf_stage_grad_sqnorm_static", "cf_static_scratch_bytes",
     "cf_adam_scratch_bytes", "cf_adam_step_with_sqnorm",
+    "cf_plan_recovery", "cf_plus_stage_order",
 )
 
 
@@ -52,6 +54,11 @@ class CfTensor(ctypes.Structure):
 class CfAdamParams(ctypes.Structure):
     _fields_ = [("learning_rate", ctypes.c_double), ("beta1", ctypes.c_double), ("beta2", ctypes.c_double),
                 ("epsilon", ctypes.c_double), ("step", ctypes.c_uint64)]
+
+
+class CfRecoveryStep(ctypes.Structure):
+    _fields_ = [("lost", ctypes.c_uint32), ("kind", ctypes.c_int32), ("prev", ctypes.c_uint32),
+                ("next", ctypes.c_uint32)]
 
 
 class CfTuning(ctypes.Structure):
@@ -128,6 +135,10 @@ def load_library():
     lib.cf_recover_stage_with_weights.argtypes = [vp, vp, vp, ctypes.c_double, ctypes.c_double, vp, vp]
     lib.cf_recovered_learning_rate.restype = ctypes.c_double
     lib.cf_recovered_learning_rate.argtypes = [ctypes.c_double]
+    lib.cf_plan_recovery.restype = i32
+    lib.cf_plan_recovery.argtypes = [u32, ctypes.POINTER(u32), u32, ctypes.c_int, ctypes.POINTER(CfRecoveryStep)]
+    lib.cf_plus_stage_order.restype = i32
+    lib.cf_plus_stage_order.argtypes = [u32, u64, ctypes.POINTER(u32)]
     lib.cf_copy_stage.restype = i32
     lib.cf_copy_stage.argtypes = [vp, vp, vp, vp]
     lib.cf_read_flags.restype = i32
@@ -417,6 +428,27 @@ def cf_recover_stage_with_weights(ctx: Context, prev: Stage, next: Stage, omega_
 def cf_recovered_learning_rate(learning_rate: float) -> float:
     """1.1 x the stage's current learning rate (Algorithm 1, third step)."""
     return float(load_library().cf_recovered_learning_rate(float(learning_rate)))
+
+
+def cf_plan_recovery(num_stages: int, lost, checkfree_plus: bool = False):
+    """[(lost, kind, prev, next), ...] for the lost stages (0-based), kind being
+    CF_RECOVER_WEIGHTED_AVG or CF_RECOVER_COPY; raises CheckFreeError when a stage
+    cannot be rebuilt (an end stage without CheckFree+, neighbouring stages lost
+    together).  Host logic only."""
+    lost = [int(i) for i in lost]
+    arr = (ctypes.c_uint32 * max(1, len(lost)))(*lost)
+    steps = (CfRecoveryStep * max(1, len(lost)))()
+    _check(load_library().cf_plan_recovery(int(num_stages), arr, len(lost), int(bool(checkfree_plus)), steps),
+           "cf_plan_recovery")
+    return [(s.lost, s.kind, s.prev, s.next) for s in steps[:len(lost)]]
+
+
+def cf_plus_stage_order(num_stages: int, microbatch: int):
+    """The stage that runs at each pipeline position for this microbatch under
+    CheckFree+ (first two and last two stages exchanged on odd microbatches)."""
+    order = (ctypes.c_uint32 * max(1, int(num_stages)))()
+    _check(load_library().cf_plus_stage_order(int(num_stages), int(microbatch), order), "cf_plus_stage_order")
+    return list(order[:int(num_stages)])
 
 
 def cf_copy_stage(ctx: Context, src: Stage, dst: Stage, stream=None):

@@ -748,6 +748,57 @@ cf_status cf_adam_step_with_sqnorm(cf_ctx *ctx, cf_stage *weights, cf_stage *exp
 
 double cf_recovered_learning_rate(double learning_rate) { return CF_RECOVERY_LR_FACTOR * learning_rate; }
 
+cf_status cf_plan_recovery(uint32_t num_stages, const uint32_t *lost, uint32_t n_lost, int checkfree_plus,
+                           cf_recovery_step *steps)
+{
+    if (n_lost == 0) return CF_OK;
+    if (!lost || !steps) return CF_ERR_NULL;
+    for (uint32_t k = 0; k < n_lost; ++k) {
+        if (lost[k] >= num_stages) return CF_ERR_LIMIT;
+        for (uint32_t j = 0; j < k; ++j)
+            if (lost[j] == lost[k]) return CF_ERR_LIMIT;
+    }
+    const auto alive = [&](uint32_t stage) {
+        for (uint32_t k = 0; k < n_lost; ++k)
+            if (lost[k] == stage) return false;
+        return true;
+    };
+    const auto step_for = [&](uint32_t i) {
+        cf_recovery_step s;
+        s.lost = i;
+        if (i == 0 || i == num_stages - 1) {
+            s.kind = CF_RECOVER_COPY;
+            s.prev = s.next = (i == 0) ? 1u : num_stages - 2u;
+        } else {
+            s.kind = CF_RECOVER_WEIGHTED_AVG;
+            s.prev = i - 1u;
+            s.next = i + 1u;
+        }
+        return s;
+    };
+    // nothing is written unless every lost stage can be rebuilt
+    for (uint32_t k = 0; k < n_lost; ++k) {
+        if (num_stages < 2) return CF_ERR_LIMIT;   // a single stage has no neighbour at all
+        const cf_recovery_step s = step_for(lost[k]);
+        if (s.kind == CF_RECOVER_COPY && !checkfree_plus) return CF_ERR_VALUE;
+        if (!alive(s.prev) || !alive(s.next)) return CF_ERR_VALUE;
+    }
+    for (uint32_t k = 0; k < n_lost; ++k) steps[k] = step_for(lost[k]);
+    return CF_OK;
+}
+
+cf_status cf_plus_stage_order(uint32_t num_stages, uint64_t microbatch, uint32_t *order)
+{
+    if (!order) return CF_ERR_NULL;
+    if (num_stages < 4) return CF_ERR_LIMIT;
+    for (uint32_t p = 0; p < num_stages; ++p) order[p] = p;
+    if (microbatch & 1u) {
+        std::swap(order[0], order[1]);
+        std::swap(order[num_stages - 2], order[num_stages - 1]);
+    }
+    return CF_OK;
+}
+
 cf_status cf_copy_stage_range(cf_ctx *ctx, const cf_stage *src, cf_stage *dst, uint32_t first_chunk,
                               uint32_t n_chunks, void *stream)
 {

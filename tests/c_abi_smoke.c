@@ -43,6 +43,19 @@ static int host_only(void)
     CHECK(cf_workspace_bytes() >= 8);
     CHECK(cf_stage_table_bytes(NULL, d, 1) == UINT64_MAX);
     CHECK(cf_ctx_create_in(0, NULL, NULL, 256, NULL, NULL) == CF_ERR_NULL);
+    {
+        /* an 8-stage pipeline loses its first stage and stage 4 */
+        const uint32_t lost[2] = {0, 4};
+        cf_recovery_step steps[2];
+        uint32_t order[8];
+        CHECK(cf_plan_recovery(8, lost, 2, 0, steps) == CF_ERR_VALUE);     /* CheckFree alone cannot rebuild an end stage */
+        CHECK(cf_plan_recovery(8, lost, 2, 1, steps) == CF_OK);
+        CHECK(steps[0].kind == CF_RECOVER_COPY && steps[0].prev == 1 && steps[0].next == 1);
+        CHECK(steps[1].kind == CF_RECOVER_WEIGHTED_AVG && steps[1].prev == 3 && steps[1].next == 5);
+        CHECK(cf_plus_stage_order(8, 3, order) == CF_OK);
+        CHECK(order[0] == 1 && order[1] == 0 && order[2] == 2 && order[6] == 7 && order[7] == 6);
+        CHECK(cf_plus_stage_order(8, 4, order) == CF_OK && order[0] == 0 && order[7] == 7);
+    }
     return 0;
 }
 

@@ -135,6 +135,65 @@ def test_recovered_learning_rate(lib):
     assert lib.cf_recover_stage_with_weights(None, None, None, 1.0, 1.0, None, None) == cf.CF_ERR_NULL
 
 
+def test_recovery_plan_matches_the_oracle_on_every_subset(lib):
+    # Algorithm 1 / CheckFree+ / "consecutive stages: no": the library's plan against the oracle's,
+    # for every set of lost stages of pipelines of 2..6 stages, in two orders of the lost list
+    import itertools
+    import oracle
+    kinds = {"average": cf.CF_RECOVER_WEIGHTED_AVG, "copy": cf.CF_RECOVER_COPY}
+    for s in range(2, 7):
+        for n in range(s + 1):
+            for lost in itertools.combinations(range(s), n):
+                for order in (lost, lost[::-1]):
+                    for plus in (False, True):
+                        try:
+                            want = oracle.recovery_plan(s, order, plus)
+                        except ValueError:
+                            with pytest.raises(cf.CheckFreeError) as e:
+                                cf.cf_plan_recovery(s, order, plus)
+                            assert e.value.status == cf.CF_ERR_VALUE
+                            continue
+                        got = cf.cf_plan_recovery(s, order, plus)
+                        assert [g[0] for g in got] == list(order)
+                        for g, w in zip(got, want):
+                            assert g[1] == kinds[w[0]] and g[2] == w[1] and g[3] == w[-1]
+
+
+def test_recovery_plan_errors_write_nothing(lib):
+    u32 = ctypes.c_uint32
+    steps = (cf.CfRecoveryStep * 3)()
+    for st in steps:
+        st.lost = st.prev = st.next = 777
+    def call(s, lost, plus):
+        arr = (u32 * max(1, len(lost)))(*lost)
+        return lib.cf_plan_recovery(s, arr, len(lost), plus, steps)
+    assert call(8, [3, 4], 1) == cf.CF_ERR_VALUE           # neighbours lost together
+    assert call(8, [2, 0], 0) == cf.CF_ERR_VALUE           # the first stage, without CheckFree+
+    assert call(8, [2, 8], 1) == cf.CF_ERR_LIMIT           # no such stage
+    assert call(8, [2, 5, 2], 1) == cf.CF_ERR_LIMIT        # named twice
+    assert call(1, [0], 1) == cf.CF_ERR_LIMIT              # a single stage has no neighbour
+    assert call(0, [0], 1) == cf.CF_ERR_LIMIT
+    assert all(st.lost == 777 and st.prev == 777 and st.next == 777 for st in steps)
+    assert lib.cf_plan_recovery(8, None, 2, 1, steps) == cf.CF_ERR_NULL
+    assert lib.cf_plan_recovery(8, (u32 * 1)(3), 1, 1, None) == cf.CF_ERR_NULL
+    assert lib.cf_plan_recovery(8, None, 0, 1, None) == cf.CF_OK
+    assert call(8, [7, 3, 0], 1) == cf.CF_OK
+    assert [(st.lost, st.kind, st.prev, st.next) for st in steps] == [
+        (7, cf.CF_RECOVER_COPY, 6, 6), (3, cf.CF_RECOVER_WEIGHTED_AVG, 2, 4), (0, cf.CF_RECOVER_COPY, 1, 1)]
+
+
+def test_plus_stage_order_matches_the_oracle(lib):
+    import oracle
+    for s in range(4, 12):
+        for mb in (0, 1, 2, 3, 10, 11, 2 ** 40, 2 ** 40 + 1):
+            assert cf.cf_plus_stage_order(s, mb) == oracle.plus_stage_order(s, mb)
+    order = (ctypes.c_uint32 * 4)(9, 9, 9, 9)
+    for s in (0, 1, 2, 3):
+        assert lib.cf_plus_stage_order(s, 1, order) == cf.CF_ERR_LIMIT
+    assert list(order) == [9, 9, 9, 9]
+    assert lib.cf_plus_stage_order(4, 1, None) == cf.CF_ERR_NULL
+
+
 def test_stage_pair_check_shapes_and_dtypes(lib):
     F, H = cf.CF_F32, cf.CF_BF16
     A = [(0x1000, 100, F), (0x2000, 7, H), (0, 0, F)]
