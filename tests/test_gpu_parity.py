@@ -292,12 +292,13 @@ def test_blend_ragged_stage(ctx, dev, dtype):
         assert_blend_close(np_stage(out), want)
 
 
-@pytest.mark.parametrize("chunk_bytes", [4096, 8192, 65536, 1 << 20])
+@pytest.mark.parametrize("chunk_bytes", [4096, 8192, 65536, 1 << 20, 4 << 20])
 @pytest.mark.parametrize("dtype", ["f32", "bf16"])
 def test_blend_copy_and_sqnorm_for_other_chunk_sizes(dev, dtype, chunk_bytes):
     """Chunk and tile boundaries move with the chunk size; results must not."""
     c = cf.Context(0, chunk_bytes=chunk_bytes)
-    shapes = workloads.ragged_shapes(5) + [(3 * 65536 + 17,), (1024,), (2048,), (1025,), (262144,)]
+    shapes = workloads.ragged_shapes(5) + [(3 * 65536 + 17,), (1024,), (2048,), (1025,), (262144,),
+                                           ((1 << 20) + 9,)]          # the last one crosses even a 4 MiB chunk
     a, b = _draw_pair(dev, shapes, dtype, 27)
     out = [torch.full_like(t, float("nan")) for t in a]
     w = _omega(dev, 3.7e-3, 1.9e-2)
