@@ -68,6 +68,9 @@ def parse():
     p.add_argument("--no-graph", action="store_true", help="skip the graph-replayed step")
     p.add_argument("--only-step", action="store_true",
                    help="the timed steps and nothing else (for profiling): implies all --no-* switches")
+    p.add_argument("--size-sweep", action="store_true",
+                   help="instead of the benchmark: bandwidth of the norm, the blend (fp32, bf16) and the copy for "
+                        "single-tensor stages of 4 MiB .. 2 GiB, cold rotating buffer sets; prints one JSON line")
     p.add_argument("--cpu-seconds", type=float, default=15.0, help="target CPU time of the oracle baseline")
     p.add_argument("--shape", type=str, default=None, help="override the stage shape: d,ffn,layers (exploration only)")
     p.add_argument("--sets", type=int, default=0,
@@ -246,6 +249,9 @@ def main():
     if args.chunk_bytes:
         tuning["chunk_bytes"] = args.chunk_bytes
     ctx = cf.Context(0, **tuning)
+    if args.size_sweep:
+        print(json.dumps(size_sweep(ctx, cf, torch)))
+        return 0
 
     run = Runner(args.config, args, ctx, cf, torch, workloads, shape)
     spec = run.spec
@@ -528,6 +534,55 @@ def measure_replica_refresh(run, ctx, cf, torch, reps=20):
 
 
 _ceiling_lib = None
+
+
+def size_sweep(ctx, cf, torch, sizes_mib=(4, 8, 16, 32, 64, 128, 256, 512, 1024, 2048)):
+    """How the three streaming kernels ramp up with the stage size: one flat tensor per stage, buffer
+    sets rotated so that every launch finds its data outside the last-level cache (at least 1 GiB is
+    cycled through), best of three timed series of back-to-back launches (dispatch gaps included)."""
+    import math
+    dev = ctx.device
+    stream = torch.cuda.current_stream()
+    weights = torch.tensor([1.5, 2.5], dtype=torch.float64, device=dev)
+    omega = torch.zeros(1, dtype=torch.float64, device=dev)
+    rows = []
+    for mib in sizes_mib:
+        nbytes = mib << 20
+        n_sets = max(1, math.ceil((1 << 30) / (3 * nbytes)))
+        row = {"MiB_per_stream": mib, "buffer_sets_rotated": n_sets}
+        for what, dtype, streams in (("norm", torch.float32, 1), ("blend_fp32", torch.float32, 3),
+                                     ("blend_bf16", torch.bfloat16, 3), ("copy", torch.float32, 2)):
+            n = nbytes // (2 if dtype == torch.bfloat16 else 4)
+            sets = [[torch.empty(n, dtype=torch.float32, device=dev).normal_(0, 1e-2).to(dtype) for _ in range(3)]
+                    for _ in range(n_sets)]
+            stages = [[cf.Stage(ctx, [t]) for t in st] for st in sets]
+
+            def launch(k):
+                a, b, o = stages[k % n_sets]
+                if what == "norm":
+                    cf.cf_stage_grad_sqnorm(ctx, [a], omega, stream)
+                elif what == "copy":
+                    cf.cf_copy_stage(ctx, a, o, stream)
+                else:
+                    cf.cf_recover_stage_weighted_avg(ctx, a, b, weights[0:1], weights[1:2], o, stream)
+
+            reps = max(20, min(2000, int(0.03 / (3 * nbytes / 6.5e12))))
+            best = float("inf")
+            for _ in range(3):
+                for k in range(max(10, reps // 5)):
+                    launch(k)
+                e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+                e0.record(stream)
+                for k in range(reps):
+                    launch(k)
+                e1.record(stream)
+                e1.synchronize()
+                best = min(best, e0.elapsed_time(e1) / reps)
+            row[what] = {"us": round(best * 1e3, 2), "GBps": round(streams * nbytes / (best * 1e-3) / 1e9, 1)}
+            del sets, stages
+        rows.append(row)
+    return {"what": "bandwidth over stage size (algorithmic bytes / time per call; norm = both passes of one stage)",
+            "rows": rows}
 
 
 def ceiling_library():
