@@ -21,6 +21,7 @@ metric is quoted on).  With the default configuration the same line also carries
 
     python bench.py [--gpus 1] [--steps K] [--warmup W] [--config 1..5]
                     [--no-cpu-baseline] [--no-ceilings] [--no-per-config] [--no-setup] [--no-graph]
+    python bench.py --size-sweep      (another line: the three kernels from 4 MiB to 2 GiB per stream)
 """
 import argparse
 import ctypes
