@@ -42,8 +42,8 @@ HBM_PEAK_GBPS = 8000.0          # MI355X HBM3E, vendor figure
 # profile named below, not measured in this run, and valid only for the kernel sources it was taken
 # on: reported as null once those have changed.
 TRAFFIC_PROFILE = "profiles/cf_kernels_hbm_traffic_pmc.md"
-TRAFFIC_KERNEL_SHA256 = "282b6c1b31554b10f3afe433eb2170063986b17ee8249710d3d237bec2a88712"
-TRAFFIC_BYTES_PER_LAUNCH = {(3, "cf_blend_kernel"): 2471145000}
+TRAFFIC_KERNEL_SHA256 = "b001382d9ee5de9dedbba6b64b36fbf2daa43f39ef5ecadf83ee183af2fd8eec"
+TRAFFIC_BYTES_PER_LAUNCH = {(3, "cf_blend_kernel"): 2471142000}
 
 
 def kernel_sources_sha256():

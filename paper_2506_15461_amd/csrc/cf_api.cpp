@@ -659,7 +659,7 @@ cf_status recover_impl(cf_ctx *ctx, const cf_stage *prev, const cf_stage *next, 
     if (!guard.ok()) return CF_ERR_HIP;
     if (cf_launch_blend(prev->d_chunks, next->d_chunks, lost->d_chunks, lost->n_chunks, ctx->tile_shift,
                         d_omega_prev, d_omega_next, h_omega_prev, h_omega_next, ctx->d_words,
-                        static_cast<hipStream_t>(stream)) != hipSuccess)
+                        lost->nbytes >= CF_BLEND_HOLD_MIN_BYTES, static_cast<hipStream_t>(stream)) != hipSuccess)
         return CF_ERR_HIP;
     return CF_OK;
 }
@@ -810,7 +810,10 @@ cf_status cf_copy_stage_range(cf_ctx *ctx, const cf_stage *src, cf_stage *dst, u
     if (n_chunks == 0) return CF_OK;
     DeviceGuard guard(ctx->device);
     if (!guard.ok()) return CF_ERR_HIP;
-    if (cf_launch_copy(src->d_chunks, dst->d_chunks, first_chunk, n_chunks, ctx->tile_shift,
+    // The range's size is at most n_chunks whole chunks; whether the stores are held back is a matter of
+    // speed only, so the upper bound serves.
+    const bool hold = (uint64_t)n_chunks * ctx->tuning.chunk_bytes >= CF_COPY_HOLD_MIN_BYTES;
+    if (cf_launch_copy(src->d_chunks, dst->d_chunks, first_chunk, n_chunks, ctx->tile_shift, hold,
                        static_cast<hipStream_t>(stream)) != hipSuccess)
         return CF_ERR_HIP;
     return CF_OK;

@@ -92,9 +92,15 @@ hipError_t cf_launch_sqnorm_tensors(const double *partials, const uint32_t *tens
 
 // One workgroup per tile; a chunk holds at most 2^tile_shift tiles of CF_TILE_BYTES.
 // The weights are read from d_omega_* when those are non-null, else taken from h_omega_*.
+// hold_stores: every wavefront holds its vector store back a little (fp32 tensors; pays on large stages only).
 hipError_t cf_launch_blend(const CfChunk *prev, const CfChunk *next, const CfChunk *lost, uint32_t n_chunks,
                            uint32_t tile_shift, const double *d_omega_prev, const double *d_omega_next,
-                           double h_omega_prev, double h_omega_next, uint32_t *words, hipStream_t stream);
+                           double h_omega_prev, double h_omega_next, uint32_t *words, bool hold_stores,
+                           hipStream_t stream);
+
+// Sizes from which holding the stores back pays (bytes of the written stage, or of the copied range).
+constexpr uint64_t CF_BLEND_HOLD_MIN_BYTES = 448ull << 20;
+constexpr uint64_t CF_COPY_HOLD_MIN_BYTES = 64ull << 20;
 
 // Scalars of one Adam step, prepared by the host: the bias corrections enter as reciprocals.
 struct CfAdamArgs {
@@ -116,6 +122,6 @@ hipError_t cf_launch_sqnorm_finalize(const CfSqnormArgs &args, hipStream_t strea
 
 // Chunks first_chunk .. first_chunk + n_chunks - 1 of the two tables.
 hipError_t cf_launch_copy(const CfChunk *src, const CfChunk *dst, uint32_t first_chunk, uint32_t n_chunks,
-                          uint32_t tile_shift, hipStream_t stream);
+                          uint32_t tile_shift, bool hold_stores, hipStream_t stream);
 
 #endif
