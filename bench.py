@@ -43,7 +43,7 @@ HBM_PEAK_GBPS = 8000.0          # MI355X HBM3E, vendor figure
 # on: reported as null once those have changed.
 TRAFFIC_PROFILE = "profiles/cf_kernels_hbm_traffic_pmc.md"
 TRAFFIC_KERNEL_SHA256 = "b001382d9ee5de9dedbba6b64b36fbf2daa43f39ef5ecadf83ee183af2fd8eec"
-TRAFFIC_BYTES_PER_LAUNCH = {(3, "cf_blend_kernel"): 2471142000}
+TRAFFIC_BYTES_PER_LAUNCH = {(3, "cf_blend_kernel"): 2471127000}
 
 
 def kernel_sources_sha256():
